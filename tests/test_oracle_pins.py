@@ -1,0 +1,324 @@
+"""Pins for the CPU oracle: every oracle function is checked against something other
+than itself - brute force from the definitions with a different loop structure,
+library routines on special cases, closed forms the paper prints, and invariants.
+All tests here run without a GPU."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rekv_oracle as O
+from paper_2503_00540_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand(shape, seed):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+# ----------------------------------------------------------------------------------
+# Eq. 1 / Eq. 3 attention
+# ----------------------------------------------------------------------------------
+def brute_force_stream(q, k, v, l_x, l_l, scale):
+    """Eq. 1 token by token over a whole stream, from the definition, with a global
+    visibility rule instead of the oracle's per-chunk slices: token i (in chunk
+    c = i // l_x, which starts at t0 = c * l_x) sees key j iff t0 - l_l <= j <= i."""
+    T, Hq, D = q.shape
+    G = Hq // k.shape[1]
+    out = np.zeros((T, Hq, D))
+    rowsum = np.zeros((T, Hq))
+    for i in range(T):
+        t0 = (i // l_x) * l_x
+        js = [j for j in range(T) if j <= i and j >= t0 - l_l]
+        for h in range(Hq):
+            g = h // G
+            z = [scale * sum(q[i, h, d] * k[j, g, d] for d in range(D)) for j in js]
+            m = max(z)
+            e = [math.exp(x - m) for x in z]
+            s = sum(e)
+            rowsum[i, h] = sum(x / s for x in e)
+            for d in range(D):
+                out[i, h, d] = sum(e[n] / s * v[j, g, d] for n, j in enumerate(js))
+    return out, rowsum
+
+
+@pytest.mark.parametrize("l_x,l_l,G", [(3, 5, 2), (4, 0, 1), (2, 100, 3), (5, 4, 2)])
+def test_encode_matches_brute_force(l_x, l_l, G):
+    n_chunks, Hkv, D = 4, 2, 4
+    T = n_chunks * l_x
+    q, k, v = _rand((T, Hkv * G, D), 1), _rand((T, Hkv, D), 2), _rand((T, Hkv, D), 3)
+    ref, rowsum = brute_force_stream(q, k, v, l_x, l_l, 1 / math.sqrt(D))
+    got = O.encode_chunks(q, k, v, 0, l_x, n_chunks, l_l)
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(rowsum, 1.0, atol=1e-12)
+    # a call that starts mid-stream equals the tail of the whole-stream call
+    got_tail = O.encode_chunks(q[2 * l_x:], k, v, 2 * l_x, l_x, 2, l_l)
+    np.testing.assert_allclose(got_tail, ref[2 * l_x:], rtol=0, atol=1e-12)
+
+
+def _sdpa(q, k, v, mask=None, causal=False):
+    """torch's scaled_dot_product_attention in fp64 with the KV heads repeated."""
+    G = q.shape[1] // k.shape[1]
+    tq = torch.from_numpy(q).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(k).permute(1, 0, 2).repeat_interleave(G, 0)[None]
+    tv = torch.from_numpy(v).permute(1, 0, 2).repeat_interleave(G, 0)[None]
+    m = None if mask is None else torch.from_numpy(mask)
+    o = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=m, is_causal=causal)
+    return o[0].permute(1, 0, 2).numpy()
+
+
+def test_window_covering_stream_is_full_causal_attention():
+    T, Hq, Hkv, D, l_x = 48, 6, 2, 16, 8
+    q, k, v = _rand((T, Hq, D), 4), _rand((T, Hkv, D), 5), _rand((T, Hkv, D), 6)
+    got = O.encode_chunks(q, k, v, 0, l_x, T // l_x, l_l=T)
+    np.testing.assert_allclose(got, _sdpa(q, k, v, causal=True), atol=1e-12)
+
+
+def test_encode_matches_sdpa_with_banded_mask():
+    T, Hq, Hkv, D, l_x, l_l = 60, 4, 2, 8, 6, 15
+    q, k, v = _rand((T, Hq, D), 7), _rand((T, Hkv, D), 8), _rand((T, Hkv, D), 9)
+    i = np.arange(T)[:, None]
+    j = np.arange(T)[None, :]
+    mask = (j <= i) & (j >= (i // l_x) * l_x - l_l)
+    got = O.encode_chunks(q, k, v, 0, l_x, T // l_x, l_l)
+    np.testing.assert_allclose(got, _sdpa(q, k, v, mask=mask), atol=1e-12)
+
+
+def test_encode_invariants():
+    T, Hq, Hkv, D, l_x, l_l = 40, 4, 2, 8, 5, 10
+    q, k, v = _rand((T, Hq, D), 10), _rand((T, Hkv, D), 11), _rand((T, Hkv, D), 12)
+    out, probs = O.encode_chunks(q, k, v, 0, l_x, T // l_x, l_l, return_probs=True)
+    for p in probs:                                    # softmax rows sum to 1
+        np.testing.assert_allclose(p.sum(axis=1), 1.0, atol=1e-13)
+        assert (p >= 0).all()
+    # masked keys get exactly zero probability: the strict upper triangle of the chunk
+    p_last = probs[-1]
+    assert (np.triu(p_last[:, -l_x:], 1) == 0).all() and (p_last[:, :-l_x] > 0).all()
+    # the output lies in the hull of the visible value rows, per dimension
+    for c in range(T // l_x):
+        t0 = c * l_x
+        w0 = max(0, t0 - l_l)
+        for i in range(l_x):
+            vis = v[w0:t0 + i + 1]
+            for h in range(Hq):
+                g = h // (Hq // Hkv)
+                assert (out[t0 + i, h] <= vis[:, g].max(0) + 1e-12).all()
+                assert (out[t0 + i, h] >= vis[:, g].min(0) - 1e-12).all()
+    # all visible values equal -> the output is that row
+    vc = np.broadcast_to(_rand((1, Hkv, D), 13), v.shape).copy()
+    oc = O.encode_chunks(q, k, vc, 0, l_x, T // l_x, l_l)
+    np.testing.assert_allclose(oc, np.repeat(vc, Hq // Hkv, axis=1), atol=1e-12)
+    # softmax shift: adding one constant vector to every key changes nothing
+    shift = _rand((1, Hkv, D), 14)
+    np.testing.assert_allclose(O.encode_chunks(q, k + shift, v, 0, l_x, T // l_x, l_l), out, atol=1e-11)
+    # causality: what comes after a chunk cannot change it (bitwise)
+    k2, v2 = k.copy(), v.copy()
+    k2[3 * l_x:] += 1.0
+    v2[3 * l_x:] -= 2.0
+    np.testing.assert_array_equal(O.encode_chunks(q[:3 * l_x], k2, v2, 0, l_x, 3, l_l), out[:3 * l_x])
+    # what fell out of the window cannot change it either
+    k3 = k.copy()
+    k3[:T - l_x - l_l] = 7.0
+    np.testing.assert_array_equal(
+        O.encode_chunks(q[-l_x:], k3, v, T - l_x, l_x, 1, l_l), out[-l_x:])
+    # scale override is honoured
+    o_s = O.encode_chunks(q, k, v, 0, l_x, T // l_x, l_l, scale=0.0)   # uniform attention
+    np.testing.assert_allclose(o_s[0, 0], v[0, 0], atol=1e-12)
+    np.testing.assert_allclose(o_s[l_x - 1, 0], v[:l_x, 0].mean(0), atol=1e-12)
+
+
+def test_window_zero_first_token_returns_own_value():
+    T, l_x = 12, 4
+    q, k, v = _rand((T, 2, 4), 15), _rand((T, 1, 4), 16), _rand((T, 1, 4), 17)
+    out = O.encode_chunks(q, k, v, 0, l_x, T // l_x, l_l=0)
+    for c in range(T // l_x):
+        np.testing.assert_allclose(out[c * l_x], np.repeat(v[c * l_x], 2, 0), atol=1e-13)
+
+
+def test_chunk_size_matters_only_when_window_is_shorter_than_the_past():
+    T, D = 24, 8
+    q, k, v = _rand((T, 2, D), 18), _rand((T, 2, D), 19), _rand((T, 2, D), 20)
+    a = O.encode_chunks(q, k, v, 0, 4, 6, l_l=T)
+    b = O.encode_chunks(q, k, v, 0, 6, 4, l_l=T)
+    np.testing.assert_allclose(a, b, atol=1e-12)
+    a = O.encode_chunks(q, k, v, 0, 4, 6, l_l=5)
+    b = O.encode_chunks(q, k, v, 0, 6, 4, l_l=5)
+    assert np.abs(a - b).max() > 1e-3          # the window is anchored at the chunk start
+
+
+def test_qa_attention_against_library_and_invariants():
+    n_ret, n_q, Hq, Hkv, D = 21, 5, 4, 2, 8
+    q = _rand((n_q, Hq, D), 21)
+    kr, vr = _rand((n_ret, Hkv, D), 22), _rand((n_ret, Hkv, D), 23)
+    ks, vs = _rand((n_q, Hkv, D), 24), _rand((n_q, Hkv, D), 25)
+    got, probs = O.qa_attention(q, kr, vr, ks, vs, return_probs=True)
+    # library special case: Eq. 3 with R in front is the tail of a full causal attention
+    # whose first n_ret queries are discarded
+    qq = np.concatenate([_rand((n_ret, Hq, D), 26), q])
+    full = _sdpa(qq, np.concatenate([kr, ks]), np.concatenate([vr, vs]), causal=True)
+    np.testing.assert_allclose(got, full[n_ret:], atol=1e-12)
+    for p in probs:
+        np.testing.assert_allclose(p.sum(axis=1), 1.0, atol=1e-13)
+    # without positional terms the result does not depend on the order of retrieved tokens
+    perm = np.random.default_rng(0).permutation(n_ret)
+    np.testing.assert_allclose(O.qa_attention(q, kr[perm], vr[perm], ks, vs), got, atol=1e-12)
+    # no retrieved tokens at all: plain causal self-attention of the question
+    np.testing.assert_allclose(O.qa_attention(q, kr[:0], vr[:0], ks, vs),
+                               _sdpa(q, ks, vs, causal=True), atol=1e-12)
+    # Eq. 3 equals Eq. 1 with R as the window and the question as the chunk
+    enc = O.encode_chunks(q, np.concatenate([kr, ks]), np.concatenate([vr, vs]), n_ret, n_q, 1, n_ret)
+    np.testing.assert_allclose(got, enc, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------------
+# frame vectors, question vector, Eq. 2 scores
+# ----------------------------------------------------------------------------------
+def test_frame_keys():
+    F, Nf, Hkv, D = 7, 5, 3, 4
+    k = _rand((F * Nf + 3, Hkv, D), 30)          # trailing tokens of an unfinished frame are ignored
+    got = O.frame_keys(k, F, Nf)
+    assert got.shape == (F, Hkv * D)
+    np.testing.assert_allclose(got, k[:F * Nf].reshape(F, Nf, Hkv * D).mean(axis=1), atol=1e-14)
+    # element by element from the definition
+    for f in (0, 3, 6):
+        for g in range(Hkv):
+            for d in range(D):
+                ref = sum(k[f * Nf + j, g, d] for j in range(Nf)) / Nf
+                assert abs(got[f, g * D + d] - ref) < 1e-14
+    const = np.broadcast_to(_rand((1, Hkv, D), 31), (F * Nf, Hkv, D))
+    np.testing.assert_allclose(O.frame_keys(const, F, Nf), np.tile(const[0].reshape(1, -1), (F, 1)), atol=1e-14)
+    k2 = _rand(k.shape, 32)
+    np.testing.assert_allclose(O.frame_keys(2 * k - 3 * k2, F, Nf),
+                               2 * got - 3 * O.frame_keys(k2, F, Nf), atol=1e-13)
+
+
+def test_question_vector():
+    Nq, Hq, Hkv, D = 6, 6, 2, 4
+    G = Hq // Hkv
+    q = _rand((Nq, Hq, D), 33)
+    got = O.question_vector(q, Hkv)
+    assert got.shape == (Hkv * D,)
+    for g in range(Hkv):
+        for d in range(D):
+            ref = sum(q[t, g * G + i, d] for t in range(Nq) for i in range(G)) / (Nq * G)
+            assert abs(got[g * D + d] - ref) < 1e-14
+    # without grouping (Hq == Hkv) it is the plain token mean of the concatenated heads
+    q1 = _rand((Nq, Hkv, D), 34)
+    np.testing.assert_allclose(O.question_vector(q1, Hkv), q1.reshape(Nq, -1).mean(0), atol=1e-14)
+
+
+def test_cosine_scores():
+    F, Dp = 50, 24
+    fv, qv = _rand((F, Dp), 35), _rand((Dp,), 36)
+    s = O.cosine_scores(fv, qv)
+    ref = torch.nn.functional.cosine_similarity(torch.from_numpy(fv), torch.from_numpy(qv)[None], dim=1)
+    np.testing.assert_allclose(s, ref.numpy(), atol=1e-13)
+    assert (np.abs(s) <= 1 + 1e-13).all()
+    np.testing.assert_allclose(O.cosine_scores(3.7 * fv, 0.2 * qv), s, atol=1e-13)   # scale-free
+    np.testing.assert_allclose(O.cosine_scores(-fv, qv), -s, atol=1e-13)
+    np.testing.assert_allclose(O.cosine_scores(fv, qv, tau=2.0), s / 2, atol=1e-13)
+    fv[11] = qv * 5.0                                   # a frame aligned with the question
+    s = O.cosine_scores(fv, qv)
+    assert abs(s[11] - 1.0) < 1e-13 and s.argmax() == 11
+    fv[12] = 0.0                                        # zero-norm frame scores 0
+    assert O.cosine_scores(fv, qv)[12] == 0.0
+    assert (O.cosine_scores(fv, np.zeros(Dp)) == 0).all()
+    # by hand on a 2-d example: cos 45 degrees
+    np.testing.assert_allclose(O.cosine_scores(np.array([[1.0, 1.0]]), np.array([1.0, 0.0])),
+                               [math.sqrt(0.5)], atol=1e-15)
+
+
+def test_frame_whose_keys_equal_the_question_ranks_first():
+    F, Nf, Nq, Hq, Hkv, D = 20, 6, 4, 4, 2, 8
+    G = Hq // Hkv
+    k = _rand((F * Nf, Hkv, D), 37)
+    q = _rand((Nq, Hq, D), 38)
+    qv = O.question_vector(q, Hkv)
+    k[9 * Nf:10 * Nf] = qv.reshape(1, Hkv, D)           # every key of frame 9 equals q
+    idx, s = O.retrieve(O.frame_keys(k, F, Nf), q, Hkv, 3)
+    assert abs(s[9] - 1.0) < 1e-12 and s.argmax() == 9 and 9 in idx
+    # the other reading of the GQA dimension mismatch (repeat each key head G times and
+    # compare with the full Hq*D query mean) ranks the frames identically
+    fk_rep = np.repeat(O.frame_keys(k, F, Nf).reshape(F, Hkv, D), G, axis=1).reshape(F, -1)
+    s_rep = O.cosine_scores(fk_rep, q.mean(axis=0).reshape(-1))
+    assert (np.argsort(-s_rep, kind="stable") == np.argsort(-s, kind="stable")).all()
+    # the question's timestamp hides later frames
+    idx5, s5 = O.retrieve(O.frame_keys(k, F, Nf), q, Hkv, 3, n_visible=5)
+    assert len(s5) == 5 and idx5.max() < 5
+    np.testing.assert_array_equal(s5, s[:5])
+
+
+# ----------------------------------------------------------------------------------
+# top-k and gather
+# ----------------------------------------------------------------------------------
+def test_topk_against_exhaustive_sort():
+    rng = np.random.default_rng(40)
+    for F, k in [(1, 1), (5, 5), (5, 9), (64, 7), (257, 64), (1000, 1)]:
+        s = rng.standard_normal(F)
+        ref = np.sort(np.argsort(-s, kind="stable")[:k])
+        np.testing.assert_array_equal(O.topk_frames(s, k), ref)
+    # ties: quantised scores, the lower index wins
+    s = np.round(rng.standard_normal(200) * 2) / 2
+    for k in (1, 3, 10, 50, 199, 200):
+        ref = np.sort(np.argsort(-s, kind="stable")[:k])
+        np.testing.assert_array_equal(O.topk_frames(s, k), ref)
+    np.testing.assert_array_equal(O.topk_frames(np.zeros(10), 4), [0, 1, 2, 3])
+    np.testing.assert_array_equal(O.topk_frames([0.1, 0.9, 0.9, 0.5], 1), [1])
+    np.testing.assert_array_equal(O.topk_frames([0.1, 0.9, 0.9, 0.5], 3), [1, 2, 3])
+
+
+def test_gather():
+    F, Nf, Hkv, D = 9, 4, 2, 3
+    k, v = _rand((F * Nf, Hkv, D), 41), _rand((F * Nf, Hkv, D), 42)
+    gk, gv = O.gather_kv(k, v, [1, 4, 8], Nf)
+    assert gk.shape == (12, Hkv, D)
+    for n, f in enumerate([1, 4, 8]):
+        assert gk[n * Nf:(n + 1) * Nf].tobytes() == k[f * Nf:(f + 1) * Nf].tobytes()
+        assert gv[n * Nf:(n + 1) * Nf].tobytes() == v[f * Nf:(f + 1) * Nf].tobytes()
+    assert O.gather_kv(k, v, [], Nf)[0].shape[0] == 0
+
+
+# ----------------------------------------------------------------------------------
+# closed form printed in the paper; end-to-end recall of planted frames
+# ----------------------------------------------------------------------------------
+def test_kv_cache_size_closed_form():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "kv_cache_size.txt")) if not l.startswith("#")]
+    assert len(rows) == 2
+    for name, L, T, M, H, D, b, printed in rows:
+        nbytes = O.kv_cache_bytes(int(L), int(T), int(M), int(H), int(D), int(b))
+        assert round(nbytes / 2 ** 30, 1) == float(printed), name
+    assert O.kv_cache_bytes(28, 1800, 196, 4, 128) == 20_230_963_200
+
+
+def test_planted_frames_are_retrieved_c0_whole_stream():
+    """C0 end to end on the oracle: frame 7 must be the best-scoring frame, and the QA
+    attention over the retrieved KV runs."""
+    w = W.C0
+    k = W.frames_k(w, 0, w.n_frames)
+    v = W.frames_v(w, 0, w.n_frames)
+    q = W.frames_q(w, 0, w.n_frames)
+    out = O.encode_chunks(q, k, v, 0, w.l_x, w.n_frames // w.chunk_frames, w.l_l)
+    assert out.shape == q.shape and np.isfinite(out).all()
+    qq, qk, qv = W.question_qkv(w)
+    idx, s = O.retrieve(O.frame_keys(k, w.n_frames, w.tokens_per_frame), qq, w.n_kv_heads, w.top_k)
+    assert s.argmax() == 7 and 7 in idx and len(idx) == 4
+    rk, rv = O.gather_kv(k, v, idx, w.tokens_per_frame)
+    assert rk.shape[0] == 64
+    o = O.qa_attention(qq, rk, rv, qk, qv)
+    assert o.shape == qq.shape and np.isfinite(o).all()
+
+
+def test_planted_recall_at_7b_shapes():
+    """Analogue of the paper's recall metric (share of question-relevant frames that are
+    retrieved): on the synthetic stream all planted frames must come back."""
+    w = W.C1.scaled(n_frames=64)
+    fk = O.frame_keys(W.frames_k(w, 0, w.n_frames), w.n_frames, w.tokens_per_frame)
+    for qi in range(3):
+        qq, _, _ = W.question_qkv(w, qi)
+        idx, s = O.retrieve(fk, qq, w.n_kv_heads, w.top_k)
+        planted = W.planted_frames(w, qi)
+        assert set(planted) <= set(idx)
+        assert set(np.argsort(-s)[:len(planted)]) == set(planted)
