@@ -1,0 +1,176 @@
+/*
+ * rekv.h - C ABI of the ReKV hot path for AMD MI355X (gfx950).
+ *
+ * ReKV ("Streaming Video Question-Answering with In-context Video KV-Cache
+ * Retrieval") changes only the attention of a decoder Video-LLM:
+ *   - the video stream is encoded chunk by chunk with sliding-window attention
+ *     (method section, Eq. 1),
+ *   - each frame keeps the mean of its key vectors as a representative vector, a
+ *     question is pooled the same way, frames are ranked by cosine similarity
+ *     (Eq. 2 with tau = 1) and the r best frames' KV is reloaded onto the GPU
+ *     (internal video KV-cache retrieval),
+ *   - the question tokens attend to the retrieved KV and to themselves (Eq. 3).
+ * This library is those steps for one attention layer on one GPU.  The Q/K/V
+ * projections, RoPE and the rest of the model stay with the caller.
+ *
+ * Conventions shared by every call
+ *   - Pointers are DEVICE pointers unless a parameter says "host".
+ *   - Layout is token-major and dense: Q and O are [tokens, Hq, D]; K and V are
+ *     [tokens, Hkv, D]; the element type is the context's dtype (fp32 or bf16).
+ *     Query head h uses KV head h / (Hq / Hkv).
+ *   - The caller owns every buffer.  The library never frees or keeps a caller
+ *     pointer after the call's work has completed on the stream.  The context owns
+ *     a private workspace (split-KV partial results, pooled question vectors,
+ *     scores), one side stream and two events.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     are asynchronous on it, except where a parameter says otherwise.
+ *   - Every call returns a rekv_status; on error nothing has been launched and
+ *     rekv_last_error() describes the argument that was refused.  A context may be
+ *     used by one host thread at a time.
+ */
+#ifndef REKV_H
+#define REKV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rekv_ctx rekv_ctx; /* opaque */
+
+typedef enum {
+    REKV_OK = 0,
+    REKV_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, Hq % Hkv != 0, ... */
+    REKV_ERR_UNSUPPORTED = 2, /* a shape the kernels do not cover (see rekv_create) */
+    REKV_ERR_NOMEM = 3,       /* the context's workspace could not be grown */
+    REKV_ERR_HIP = 4          /* a HIP runtime call failed; message holds hipGetErrorString */
+} rekv_status;
+
+typedef enum { REKV_F32 = 0, REKV_BF16 = 1 } rekv_dtype;
+
+typedef struct {
+    int32_t n_q_heads;        /* Hq */
+    int32_t n_kv_heads;       /* Hkv, divides Hq */
+    int32_t head_dim;         /* D: 64 or 128 for bf16; a multiple of 4 up to 256 for fp32 */
+    int32_t tokens_per_frame; /* N_f > 0 */
+    int32_t dtype;            /* rekv_dtype of Q/K/V/O */
+    float softmax_scale;      /* 0 means 1/sqrt(D) */
+} rekv_shape;
+
+/* Creates a context for one layer shape on the current HIP device.  Host call; allocates
+ * the side stream and events.  *out is NULL on failure. */
+rekv_status rekv_create(const rekv_shape* shape, rekv_ctx** out);
+
+/* Waits for the side stream, frees the workspace.  NULL is accepted. */
+void rekv_destroy(rekv_ctx* ctx);
+
+/* Message of the last failed call on this context (empty string if none).  With a NULL
+ * context, the message of the last failed rekv_create on this thread. */
+const char* rekv_last_error(const rekv_ctx* ctx);
+
+/*
+ * Video stream encoding with sliding-window attention, Eq. 1.
+ *
+ * Encodes n_chunks >= 1 consecutive chunks of l_x tokens.  Chunk c starts at stream
+ * token t0 = first_token + c * l_x.  Each of its tokens attends to the local window
+ * L = the last min(l_l, t0) tokens before t0 (the same L for the whole chunk, as Eq. 1
+ * defines it) and, causally, to the chunk's tokens up to itself.  Several chunks in one
+ * call give exactly the result of one call per chunk, because the keys and values are
+ * inputs.
+ *
+ *   q        [n_chunks * l_x, Hq, D]   queries of the chunks' tokens
+ *   k_cache  [>= first_token + n_chunks * l_x, Hkv, D]  the stream's keys indexed by
+ *   v_cache  same shape                stream token, already holding the chunks' own K/V
+ *   out      [n_chunks * l_x, Hq, D]
+ *   l_l      window length in tokens (>= 0)
+ */
+rekv_status rekv_encode_chunk(rekv_ctx* ctx, const void* q, const void* k_cache,
+                              const void* v_cache, int64_t first_token, int32_t l_x,
+                              int32_t n_chunks, int32_t l_l, void* out, void* stream);
+
+/*
+ * Representative frame vectors (internal retrieval): for each frame the mean of its
+ * N_f key vectors, KV heads concatenated to D' = Hkv * D.
+ *
+ *   k           [n_frames * N_f, Hkv, D]   keys of n_frames whole frames
+ *   frame_keys  [n_frames, D'] fp32 (always fp32, accumulated in fp32)
+ */
+rekv_status rekv_frame_keys(rekv_ctx* ctx, const void* k, int32_t n_frames, float* frame_keys,
+                            void* stream);
+
+/*
+ * Internal retrieval: pooled question vector, Eq. 2 cosine scores (tau = 1), top-k.
+ *
+ * For each of n_questions questions: the question vector is the mean of its N_q query
+ * vectors, the G query heads of a KV group averaged so that it has D' entries; the score
+ * of frame f < n_frames is the cosine between that vector and frame_keys[f] (0 when either
+ * norm is 0); the k best-scoring frames are selected, ties going to the lower frame index.
+ * n_frames is the number of frames visible to the question (its timestamp cut-off).
+ *
+ *   frame_keys          [n_frames, D'] fp32 per table
+ *   frame_keys_stride   elements between the tables of consecutive questions; 0 = all
+ *                       questions share one table (many questions on one stream); a
+ *                       per-layer table per "question" gives per-layer retrieval
+ *   q_question          [n_questions, N_q, Hq, D] in the context dtype
+ *   idx                 [n_questions, k] int32: the selected frames in ascending frame
+ *                       order; entries past n_sel are -1
+ *   n_sel               [n_questions] int32: min(k, n_frames); may be NULL
+ *   scores              [n_questions, n_frames] fp32, may be NULL
+ * Limits: 1 <= k <= 4096, n_frames >= 1.
+ */
+rekv_status rekv_retrieve_topk(rekv_ctx* ctx, const float* frame_keys, int64_t frame_keys_stride,
+                               int32_t n_frames, const void* q_question, int32_t n_questions,
+                               int32_t n_q_tokens, int32_t k, int32_t* idx, int32_t* n_sel,
+                               float* scores, void* stream);
+
+/*
+ * Reload of the retrieved KV: copies the selected frames' key and value blocks into one
+ * dense buffer per question, in the order idx gives them (ascending frame index).
+ *
+ *   src_k, src_v  [n_src_frames * N_f, Hkv, D] in HBM (src_on_host = 0) or in pinned host
+ *                 memory (src_on_host = 1, host pointers; memory from hipHostMalloc)
+ *   idx           [n_questions, k] int32 on the device; entries < 0 are skipped and their
+ *                 destination block is zero-filled; entries >= n_src_frames are an error
+ *                 only on the host path (the device path skips them likewise)
+ *   dst_k, dst_v  [n_questions, k * N_f, Hkv, D] in HBM
+ * Host path: idx is copied to the host (the call blocks until `stream` reaches it), then
+ * one async copy per frame and tensor runs on the context's side stream; `stream` waits
+ * on an event for their completion, so later work on `stream` sees the data.
+ */
+rekv_status rekv_gather_kv(rekv_ctx* ctx, const void* src_k, const void* src_v,
+                           int32_t src_on_host, int32_t n_src_frames, const int32_t* idx,
+                           int32_t n_questions, int32_t k, void* dst_k, void* dst_v, void* stream);
+
+/*
+ * Question answering over the retrieved KV, Eq. 3 with X = the question tokens: every
+ * question token attends to all n_ret_tokens retrieved tokens and, causally, to the
+ * question tokens up to itself.
+ *
+ *   q, out          [n_questions, N_q, Hq, D]
+ *   k_ret, v_ret    [n_questions, n_ret_tokens, Hkv, D]   (n_ret_tokens may be 0)
+ *   k_self, v_self  [n_questions, N_q, Hkv, D]
+ */
+rekv_status rekv_qa_attention(rekv_ctx* ctx, const void* q, const void* k_ret, const void* v_ret,
+                              int32_t n_ret_tokens, const void* k_self, const void* v_self,
+                              int32_t n_questions, int32_t n_q_tokens, void* out, void* stream);
+
+/*
+ * Offload of encoded KV to RAM (the paper stores all video KV and moves what leaves the
+ * local window off the GPU).  Copies n_frames whole frames of K and V, starting at frame
+ * first_frame of the device arrays, to the same frame positions of the pinned host arrays.
+ * The copies run on the context's side stream after everything queued on `stream` so far;
+ * `stream` does not wait for them.  rekv_offload_wait() blocks the host until all offloads
+ * issued on this context have landed.
+ *
+ *   dev_k, dev_v    [>= (first_frame + n_frames) * N_f, Hkv, D] in HBM
+ *   host_k, host_v  same indexing, pinned host memory (host pointers)
+ */
+rekv_status rekv_offload_kv(rekv_ctx* ctx, const void* dev_k, const void* dev_v, void* host_k,
+                            void* host_v, int64_t first_frame, int32_t n_frames, void* stream);
+rekv_status rekv_offload_wait(rekv_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REKV_H */

@@ -1,0 +1,316 @@
+// The C ABI of librekv: argument validation, the context (workspace, side stream, events)
+// and dispatch to the kernels.  No arithmetic of the method happens in this file.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "common.h"
+
+struct rekv_ctx {
+    rekv_shape shape;
+    float scale;
+    int device;
+    void* ws;             // workspace: split-KV partials, or pooled questions + scores
+    size_t ws_bytes;
+    hipStream_t side;     // host<->device copies of offloaded KV
+    hipEvent_t ev_main;   // recorded on the caller's stream, waited on by the side stream
+    hipEvent_t ev_side;   // recorded on the side stream, waited on by the caller's stream
+    int32_t* idx_host;    // pinned staging for the index list of the host gather
+    size_t idx_host_cap;  // entries
+    char err[512];
+};
+
+namespace {
+
+thread_local char g_create_err[512] = "";
+
+rekv_status fail(rekv_ctx* ctx, rekv_status code, const char* fmt, ...) {
+    char* dst = ctx ? ctx->err : g_create_err;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, 512, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+rekv_status fail_hip(rekv_ctx* ctx, const char* what, hipError_t e) {
+    return fail(ctx, REKV_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+size_t elem_size(const rekv_ctx* c) { return c->shape.dtype == REKV_BF16 ? 2 : 4; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// Grows the context's workspace.  Freeing the old block waits for the device, so work that
+// still reads it has finished.
+rekv_status reserve(rekv_ctx* c, size_t bytes) {
+    if (bytes <= c->ws_bytes) return REKV_OK;
+    if (c->ws) {
+        hipError_t e = hipFree(c->ws);
+        c->ws = nullptr;
+        c->ws_bytes = 0;
+        if (e != hipSuccess) return fail_hip(c, "hipFree(workspace)", e);
+    }
+    bytes = (bytes + (size_t(1) << 20) - 1) & ~((size_t(1) << 20) - 1);
+    hipError_t e = hipMalloc(&c->ws, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        c->ws = nullptr;
+        return fail(c, REKV_ERR_NOMEM, "workspace of %zu bytes: %s", bytes, hipGetErrorString(e));
+    }
+    c->ws_bytes = bytes;
+    return REKV_OK;
+}
+
+rekv_status run_attention(rekv_ctx* c, const rekv::AttnProblem& p, hipStream_t stream) {
+    if (c->shape.dtype == REKV_F32) {
+        if (p.n_items > 65535)
+            return fail(c, REKV_ERR_UNSUPPORTED, "fp32 attention takes at most 65535 chunks/questions per call");
+        hipError_t e = rekv::attn_f32_launch(p, stream);
+        return e == hipSuccess ? REKV_OK : fail_hip(c, "fp32 attention launch", e);
+    }
+    const rekv::AttnPlan plan = rekv::attn_bf16_plan(p);
+    const int64_t blocks = (int64_t)p.n_items * p.n_kv_heads * plan.m_tiles * plan.n_splits;
+    if (blocks > 0x7FFFFFFF) return fail(c, REKV_ERR_UNSUPPORTED, "attention grid of %lld workgroups", (long long)blocks);
+    rekv_status s = reserve(c, plan.workspace_bytes);
+    if (s != REKV_OK) return s;
+    hipError_t e = rekv::attn_bf16_launch(p, plan, c->ws, stream);
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "bf16 attention launch", e);
+}
+
+}  // namespace
+
+extern "C" {
+
+rekv_status rekv_create(const rekv_shape* shape, rekv_ctx** out) {
+    if (out) *out = nullptr;
+    if (!shape || !out) return fail(nullptr, REKV_ERR_INVALID_ARG, "rekv_create: null argument");
+    if (shape->n_q_heads <= 0 || shape->n_kv_heads <= 0 || shape->n_q_heads % shape->n_kv_heads != 0)
+        return fail(nullptr, REKV_ERR_INVALID_ARG, "n_q_heads=%d must be a positive multiple of n_kv_heads=%d",
+                    shape->n_q_heads, shape->n_kv_heads);
+    if (shape->tokens_per_frame <= 0)
+        return fail(nullptr, REKV_ERR_INVALID_ARG, "tokens_per_frame=%d must be positive", shape->tokens_per_frame);
+    if (!(shape->softmax_scale >= 0.f) || shape->softmax_scale > 1e30f)
+        return fail(nullptr, REKV_ERR_INVALID_ARG, "softmax_scale must be finite and >= 0 (0 selects 1/sqrt(D))");
+    if (shape->dtype == REKV_BF16) {
+        if (shape->head_dim != 64 && shape->head_dim != 128)
+            return fail(nullptr, REKV_ERR_UNSUPPORTED, "bf16 kernels cover head_dim 64 and 128, not %d", shape->head_dim);
+    } else if (shape->dtype == REKV_F32) {
+        if (shape->head_dim <= 0 || shape->head_dim > 256 || shape->head_dim % 4 != 0)
+            return fail(nullptr, REKV_ERR_UNSUPPORTED, "fp32 kernels cover head_dim a multiple of 4 up to 256, not %d", shape->head_dim);
+    } else {
+        return fail(nullptr, REKV_ERR_INVALID_ARG, "dtype=%d is neither REKV_F32 nor REKV_BF16", shape->dtype);
+    }
+    rekv_ctx* c = new (std::nothrow) rekv_ctx;
+    if (!c) return fail(nullptr, REKV_ERR_NOMEM, "host allocation of the context failed");
+    memset(c, 0, sizeof(*c));
+    c->shape = *shape;
+    c->scale = shape->softmax_scale > 0.f ? shape->softmax_scale : 1.0f / sqrtf((float)shape->head_dim);
+    hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_main, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_side, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        rekv_status s = fail_hip(nullptr, "rekv_create", e);
+        rekv_destroy(c);
+        return s;
+    }
+    *out = c;
+    return REKV_OK;
+}
+
+void rekv_destroy(rekv_ctx* c) {
+    if (!c) return;
+    if (c->side) {
+        (void)hipStreamSynchronize(c->side);
+        (void)hipStreamDestroy(c->side);
+    }
+    if (c->ev_main) (void)hipEventDestroy(c->ev_main);
+    if (c->ev_side) (void)hipEventDestroy(c->ev_side);
+    if (c->ws) (void)hipFree(c->ws);
+    if (c->idx_host) (void)hipHostFree(c->idx_host);
+    delete c;
+}
+
+const char* rekv_last_error(const rekv_ctx* c) { return c ? c->err : g_create_err; }
+
+rekv_status rekv_encode_chunk(rekv_ctx* c, const void* q, const void* k_cache, const void* v_cache,
+                              int64_t first_token, int32_t l_x, int32_t n_chunks, int32_t l_l,
+                              void* out, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!q || !k_cache || !v_cache || !out) return fail(c, REKV_ERR_INVALID_ARG, "rekv_encode_chunk: null pointer");
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_encode_chunk: pointers must be 16-byte aligned");
+    if (first_token < 0 || l_x <= 0 || n_chunks <= 0 || l_l < 0)
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_encode_chunk: first_token=%lld l_x=%d n_chunks=%d l_l=%d",
+                    (long long)first_token, l_x, n_chunks, l_l);
+    if ((int64_t)l_x * (c->shape.n_q_heads / c->shape.n_kv_heads) > 0x3FFFFFFF)
+        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_encode_chunk: chunk of %d tokens is too long", l_x);
+    rekv::AttnProblem p;
+    memset(&p, 0, sizeof(p));
+    p.q = q; p.out = out;
+    p.k_a = k_cache; p.v_a = v_cache; p.k_b = k_cache; p.v_b = v_cache;
+    p.first_token = first_token; p.l_l = l_l; p.len_a = 0; p.len_b = l_x;
+    p.n_items = n_chunks; p.is_encode = 1;
+    p.n_q_heads = c->shape.n_q_heads; p.n_kv_heads = c->shape.n_kv_heads; p.head_dim = c->shape.head_dim;
+    p.scale = c->scale;
+    return run_attention(c, p, static_cast<hipStream_t>(stream));
+}
+
+rekv_status rekv_qa_attention(rekv_ctx* c, const void* q, const void* k_ret, const void* v_ret,
+                              int32_t n_ret_tokens, const void* k_self, const void* v_self,
+                              int32_t n_questions, int32_t n_q_tokens, void* out, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!q || !k_self || !v_self || !out || (n_ret_tokens > 0 && (!k_ret || !v_ret)))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_qa_attention: null pointer");
+    if (!aligned16(q) || !aligned16(k_ret) || !aligned16(v_ret) || !aligned16(k_self) || !aligned16(v_self) || !aligned16(out))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_qa_attention: pointers must be 16-byte aligned");
+    if (n_ret_tokens < 0 || n_questions <= 0 || n_q_tokens <= 0)
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_qa_attention: n_ret_tokens=%d n_questions=%d n_q_tokens=%d",
+                    n_ret_tokens, n_questions, n_q_tokens);
+    if ((int64_t)n_q_tokens * (c->shape.n_q_heads / c->shape.n_kv_heads) > 0x3FFFFFFF)
+        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_qa_attention: question of %d tokens is too long", n_q_tokens);
+    rekv::AttnProblem p;
+    memset(&p, 0, sizeof(p));
+    p.q = q; p.out = out;
+    p.k_a = k_ret ? k_ret : k_self; p.v_a = v_ret ? v_ret : v_self; p.k_b = k_self; p.v_b = v_self;
+    p.first_token = 0; p.l_l = 0; p.len_a = n_ret_tokens; p.len_b = n_q_tokens;
+    p.n_items = n_questions; p.is_encode = 0;
+    p.n_q_heads = c->shape.n_q_heads; p.n_kv_heads = c->shape.n_kv_heads; p.head_dim = c->shape.head_dim;
+    p.scale = c->scale;
+    return run_attention(c, p, static_cast<hipStream_t>(stream));
+}
+
+rekv_status rekv_frame_keys(rekv_ctx* c, const void* k, int32_t n_frames, float* frame_keys, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!k || !frame_keys) return fail(c, REKV_ERR_INVALID_ARG, "rekv_frame_keys: null pointer");
+    if (!aligned16(k)) return fail(c, REKV_ERR_INVALID_ARG, "rekv_frame_keys: k must be 16-byte aligned");
+    if (n_frames <= 0) return fail(c, REKV_ERR_INVALID_ARG, "rekv_frame_keys: n_frames=%d", n_frames);
+    hipError_t e = rekv::frame_keys_launch(k, n_frames, c->shape.tokens_per_frame,
+                                           c->shape.n_kv_heads * c->shape.head_dim, c->shape.dtype,
+                                           frame_keys, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "frame_keys launch", e);
+}
+
+rekv_status rekv_retrieve_topk(rekv_ctx* c, const float* frame_keys, int64_t frame_keys_stride,
+                               int32_t n_frames, const void* q_question, int32_t n_questions,
+                               int32_t n_q_tokens, int32_t k, int32_t* idx, int32_t* n_sel,
+                               float* scores, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!frame_keys || !q_question || !idx) return fail(c, REKV_ERR_INVALID_ARG, "rekv_retrieve_topk: null pointer");
+    if (!aligned16(frame_keys) || frame_keys_stride < 0 || frame_keys_stride % 4 != 0)
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_retrieve_topk: frame_keys must be 16-byte aligned and its stride a non-negative multiple of 4");
+    if (n_frames <= 0 || n_questions <= 0 || n_q_tokens <= 0 || k <= 0 || k > 4096)
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_retrieve_topk: n_frames=%d n_questions=%d n_q_tokens=%d k=%d (1..4096)",
+                    n_frames, n_questions, n_q_tokens, k);
+    const int d_prime = c->shape.n_kv_heads * c->shape.head_dim;
+    if ((size_t)(d_prime + 1) * sizeof(float) > 48 * 1024)
+        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_retrieve_topk: Hkv*D=%d exceeds 12287", d_prime);
+    if (n_questions > 65535) return fail(c, REKV_ERR_UNSUPPORTED, "rekv_retrieve_topk: at most 65535 questions per call");
+    const size_t qv_bytes = ((size_t)n_questions * d_prime * sizeof(float) + 255) & ~size_t(255);
+    const size_t sc_bytes = scores ? 0 : (size_t)n_questions * n_frames * sizeof(float);
+    rekv_status s = reserve(c, qv_bytes + sc_bytes);
+    if (s != REKV_OK) return s;
+    rekv::RetrieveArgs a;
+    a.frame_keys = frame_keys; a.frame_keys_stride = frame_keys_stride; a.n_frames = n_frames;
+    a.q_question = q_question; a.n_questions = n_questions; a.n_q_tokens = n_q_tokens; a.k = k;
+    a.n_q_heads = c->shape.n_q_heads; a.n_kv_heads = c->shape.n_kv_heads; a.head_dim = c->shape.head_dim;
+    a.dtype = c->shape.dtype;
+    a.idx = idx; a.n_sel = n_sel;
+    a.q_vec = static_cast<float*>(c->ws);
+    a.scores = scores ? scores : reinterpret_cast<float*>(static_cast<char*>(c->ws) + qv_bytes);
+    hipError_t e = rekv::retrieve_launch(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "retrieval launch", e);
+}
+
+rekv_status rekv_gather_kv(rekv_ctx* c, const void* src_k, const void* src_v, int32_t src_on_host,
+                           int32_t n_src_frames, const int32_t* idx, int32_t n_questions, int32_t k,
+                           void* dst_k, void* dst_v, void* stream_) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!src_k || !src_v || !idx || !dst_k || !dst_v) return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv: null pointer");
+    if (!aligned16(src_k) || !aligned16(src_v) || !aligned16(dst_k) || !aligned16(dst_v))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv: pointers must be 16-byte aligned");
+    if (n_src_frames <= 0 || n_questions <= 0 || k <= 0 || (src_on_host != 0 && src_on_host != 1))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv: n_src_frames=%d n_questions=%d k=%d src_on_host=%d",
+                    n_src_frames, n_questions, k, src_on_host);
+    const int64_t n_blocks = (int64_t)n_questions * k;
+    if (n_blocks > 0x7FFFFFFF) return fail(c, REKV_ERR_UNSUPPORTED, "rekv_gather_kv: %lld blocks", (long long)n_blocks);
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const size_t frame_bytes = (size_t)c->shape.tokens_per_frame * c->shape.n_kv_heads * c->shape.head_dim * elem_size(c);
+    if (frame_bytes % 16 != 0) return fail(c, REKV_ERR_UNSUPPORTED, "rekv_gather_kv: frame of %zu bytes is not a multiple of 16", frame_bytes);
+
+    if (!src_on_host) {
+        hipError_t e = rekv::gather_launch(src_k, src_v, n_src_frames, idx, (int)n_blocks, frame_bytes,
+                                           dst_k, dst_v, stream);
+        return e == hipSuccess ? REKV_OK : fail_hip(c, "gather launch", e);
+    }
+
+    // Host path: bring the index list to the host, then one async copy per frame and tensor
+    // on the side stream, ordered after `stream` (the destination may still be in use there)
+    // and joined back into it.
+    if ((size_t)n_blocks > c->idx_host_cap) {
+        if (c->idx_host) (void)hipHostFree(c->idx_host);
+        c->idx_host = nullptr;
+        c->idx_host_cap = 0;
+        hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&c->idx_host), (size_t)n_blocks * sizeof(int32_t), hipHostMallocDefault);
+        if (e != hipSuccess) { (void)hipGetLastError(); return fail(c, REKV_ERR_NOMEM, "pinned index staging: %s", hipGetErrorString(e)); }
+        c->idx_host_cap = (size_t)n_blocks;
+    }
+    hipError_t e = hipMemcpyAsync(c->idx_host, idx, (size_t)n_blocks * sizeof(int32_t), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipEventRecord(c->ev_main, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail_hip(c, "rekv_gather_kv: index copy", e);
+    for (int64_t b = 0; b < n_blocks; ++b)
+        if (c->idx_host[b] >= n_src_frames)
+            return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv: idx[%lld]=%d is not below n_src_frames=%d",
+                        (long long)b, c->idx_host[b], n_src_frames);
+    e = hipStreamWaitEvent(c->side, c->ev_main, 0);
+    for (int64_t b = 0; b < n_blocks && e == hipSuccess; ++b) {
+        const int32_t f = c->idx_host[b];
+        char* dk = static_cast<char*>(dst_k) + (size_t)b * frame_bytes;
+        char* dv = static_cast<char*>(dst_v) + (size_t)b * frame_bytes;
+        if (f < 0) {
+            e = hipMemsetAsync(dk, 0, frame_bytes, c->side);
+            if (e == hipSuccess) e = hipMemsetAsync(dv, 0, frame_bytes, c->side);
+            continue;
+        }
+        // runs of consecutive frames in consecutive slots move as one copy
+        int64_t run = 1;
+        while (b + run < n_blocks && c->idx_host[b + run] == f + run) ++run;
+        e = hipMemcpyAsync(dk, static_cast<const char*>(src_k) + (size_t)f * frame_bytes, run * frame_bytes, hipMemcpyHostToDevice, c->side);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(dv, static_cast<const char*>(src_v) + (size_t)f * frame_bytes, run * frame_bytes, hipMemcpyHostToDevice, c->side);
+        b += run - 1;
+    }
+    if (e == hipSuccess) e = hipEventRecord(c->ev_side, c->side);
+    if (e == hipSuccess) e = hipStreamWaitEvent(stream, c->ev_side, 0);
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "rekv_gather_kv: host copies", e);
+}
+
+rekv_status rekv_offload_kv(rekv_ctx* c, const void* dev_k, const void* dev_v, void* host_k, void* host_v,
+                            int64_t first_frame, int32_t n_frames, void* stream_) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!dev_k || !dev_v || !host_k || !host_v) return fail(c, REKV_ERR_INVALID_ARG, "rekv_offload_kv: null pointer");
+    if (first_frame < 0 || n_frames <= 0)
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_offload_kv: first_frame=%lld n_frames=%d", (long long)first_frame, n_frames);
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const size_t frame_bytes = (size_t)c->shape.tokens_per_frame * c->shape.n_kv_heads * c->shape.head_dim * elem_size(c);
+    const size_t off = (size_t)first_frame * frame_bytes, bytes = (size_t)n_frames * frame_bytes;
+    hipError_t e = hipEventRecord(c->ev_main, stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent(c->side, c->ev_main, 0);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(static_cast<char*>(host_k) + off, static_cast<const char*>(dev_k) + off, bytes, hipMemcpyDeviceToHost, c->side);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(static_cast<char*>(host_v) + off, static_cast<const char*>(dev_v) + off, bytes, hipMemcpyDeviceToHost, c->side);
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "rekv_offload_kv", e);
+}
+
+rekv_status rekv_offload_wait(rekv_ctx* c) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    hipError_t e = hipStreamSynchronize(c->side);
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "rekv_offload_wait", e);
+}
+
+}  // extern "C"

@@ -1,0 +1,88 @@
+// Internal declarations shared by the HIP sources of librekv (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rekv.h"
+
+namespace rekv {
+
+typedef __bf16 bf16_t;
+
+// One attention problem family: every batch item (a chunk of the stream, or a question)
+// attends to two key segments.  Segment A is visible to every query row; segment B is the
+// item's own tokens, visible causally (query token i sees B-token j iff j <= i).
+//   encode (Eq. 1): A = local window in the cache, B = the chunk's own K/V in the cache
+//   QA     (Eq. 3): A = retrieved KV of the question, B = the question's own K/V
+struct AttnProblem {
+    const void* q;      // [n_items * len_b, Hq, D]
+    void* out;          // same shape
+    const void* k_a;    // encode: k_cache; QA: k_ret
+    const void* v_a;
+    const void* k_b;    // encode: k_cache; QA: k_self
+    const void* v_b;
+    int64_t first_token;  // encode only
+    int32_t l_l;          // encode only: window length in tokens
+    int32_t len_a;        // QA only: retrieved tokens per question
+    int32_t len_b;        // l_x or N_q
+    int32_t n_items;      // chunks or questions
+    int32_t is_encode;
+    int32_t n_q_heads, n_kv_heads, head_dim;
+    float scale;
+};
+
+// Resolves one item's segment bases (in elements) and lengths.  Host and device.
+struct ItemSegs {
+    int64_t a_off, b_off;  // token offsets into k_a/v_a and k_b/v_b
+    int32_t len_a;
+};
+__host__ __device__ inline ItemSegs item_segments(const AttnProblem& p, int item) {
+    ItemSegs s;
+    if (p.is_encode) {
+        const int64_t t0 = p.first_token + (int64_t)item * p.len_b;
+        const int64_t w0 = t0 > p.l_l ? t0 - p.l_l : 0;
+        s.a_off = w0;
+        s.b_off = t0;
+        s.len_a = (int32_t)(t0 - w0);
+    } else {
+        s.a_off = (int64_t)item * p.len_a;
+        s.b_off = (int64_t)item * p.len_b;
+        s.len_a = p.len_a;
+    }
+    return s;
+}
+
+// Split-KV workspace need of the bf16 kernel, in bytes (0 when one split suffices).
+struct AttnPlan {
+    int32_t n_splits;
+    int32_t m_tiles;
+    size_t workspace_bytes;
+};
+AttnPlan attn_bf16_plan(const AttnProblem& p);
+hipError_t attn_bf16_launch(const AttnProblem& p, const AttnPlan& plan, void* workspace,
+                            hipStream_t stream);
+hipError_t attn_f32_launch(const AttnProblem& p, hipStream_t stream);
+
+hipError_t frame_keys_launch(const void* k, int n_frames, int tokens_per_frame, int d_prime,
+                             int dtype, float* frame_keys, hipStream_t stream);
+
+struct RetrieveArgs {
+    const float* frame_keys;
+    int64_t frame_keys_stride;
+    int32_t n_frames;
+    const void* q_question;
+    int32_t n_questions, n_q_tokens, k;
+    int32_t n_q_heads, n_kv_heads, head_dim, dtype;
+    int32_t* idx;
+    int32_t* n_sel;
+    float* scores;   // [n_questions, n_frames], never NULL here (workspace if the caller gave none)
+    float* q_vec;    // [n_questions, D'] workspace
+};
+hipError_t retrieve_launch(const RetrieveArgs& a, hipStream_t stream);
+
+hipError_t gather_launch(const void* src_k, const void* src_v, int n_src_frames, const int32_t* idx,
+                         int n_blocks, size_t frame_bytes, void* dst_k, void* dst_v,
+                         hipStream_t stream);
+
+}  // namespace rekv

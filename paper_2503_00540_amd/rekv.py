@@ -1,0 +1,240 @@
+"""Thin ctypes binding over librekv.so: same names as the C ABI, argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI (`include/rekv.h`).  PyTorch
+appears here only as the owner of device / pinned memory and of the current stream.  If the
+library has not been built the binding raises; there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, byref, c_char_p, c_float, c_int32, c_int64, c_void_p
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "librekv.so")
+
+REKV_F32, REKV_BF16 = 0, 1
+_STATUS = {0: "REKV_OK", 1: "REKV_ERR_INVALID_ARG", 2: "REKV_ERR_UNSUPPORTED",
+           3: "REKV_ERR_NOMEM", 4: "REKV_ERR_HIP"}
+_DTYPES = {"f32": (REKV_F32, torch.float32), "bf16": (REKV_BF16, torch.bfloat16)}
+
+# Every entry point include/rekv.h declares.
+SYMBOLS = ("rekv_create", "rekv_destroy", "rekv_last_error", "rekv_encode_chunk",
+           "rekv_frame_keys", "rekv_retrieve_topk", "rekv_gather_kv", "rekv_qa_attention",
+           "rekv_offload_kv", "rekv_offload_wait")
+
+
+class RekvShape(ctypes.Structure):
+    _fields_ = [("n_q_heads", c_int32), ("n_kv_heads", c_int32), ("head_dim", c_int32),
+                ("tokens_per_frame", c_int32), ("dtype", c_int32), ("softmax_scale", c_float)]
+
+
+class RekvError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads librekv.so; raises if it has not been built (python -m paper_2503_00540_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2503_00540_amd.build`; "
+                           "there is no fallback path")
+    L = ctypes.CDLL(LIB_PATH)
+    L.rekv_create.argtypes = [POINTER(RekvShape), POINTER(c_void_p)]
+    L.rekv_create.restype = c_int32
+    L.rekv_destroy.argtypes = [c_void_p]
+    L.rekv_destroy.restype = None
+    L.rekv_last_error.argtypes = [c_void_p]
+    L.rekv_last_error.restype = c_char_p
+    L.rekv_encode_chunk.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32,
+                                    c_int32, c_void_p, c_void_p]
+    L.rekv_frame_keys.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p]
+    L.rekv_retrieve_topk.argtypes = [c_void_p, c_void_p, c_int64, c_int32, c_void_p, c_int32, c_int32,
+                                     c_int32, c_void_p, c_void_p, c_void_p, c_void_p]
+    L.rekv_gather_kv.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_int32,
+                                 c_int32, c_void_p, c_void_p, c_void_p]
+    L.rekv_qa_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p,
+                                    c_int32, c_int32, c_void_p, c_void_p]
+    L.rekv_offload_kv.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32,
+                                  c_void_p]
+    L.rekv_offload_wait.argtypes = [c_void_p]
+    for name in SYMBOLS[3:]:
+        getattr(L, name).restype = c_int32
+    _lib = L
+    return L
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Rekv:
+    """One layer shape's context.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, n_q_heads: int, n_kv_heads: int, head_dim: int, tokens_per_frame: int,
+                 dtype: str = "bf16", softmax_scale: float = 0.0):
+        self.n_q_heads, self.n_kv_heads, self.head_dim = n_q_heads, n_kv_heads, head_dim
+        self.tokens_per_frame = tokens_per_frame
+        self.dtype_name = dtype
+        code, self.torch_dtype = _DTYPES[dtype]
+        self._lib = lib()
+        shape = RekvShape(n_q_heads, n_kv_heads, head_dim, tokens_per_frame, code, softmax_scale)
+        h = c_void_p()
+        st = self._lib.rekv_create(byref(shape), byref(h))
+        if st != 0:
+            raise RekvError(st, self._lib.rekv_last_error(None).decode())
+        self._h = h
+
+    @classmethod
+    def for_workload(cls, w, softmax_scale: float = 0.0) -> "Rekv":
+        return cls(w.n_q_heads, w.n_kv_heads, w.head_dim, w.tokens_per_frame, w.dtype, softmax_scale)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.rekv_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- marshalling helpers ------------------------------------------------------------
+    def _check(self, st: int):
+        if st != 0:
+            raise RekvError(st, self._lib.rekv_last_error(self._h).decode())
+
+    def _dev(self, t: torch.Tensor, dtype=None, last=None, name="tensor") -> int:
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous CUDA tensor")
+        if t.dtype != (dtype or self.torch_dtype):
+            raise ValueError(f"{name} has dtype {t.dtype}, expected {dtype or self.torch_dtype}")
+        if last is not None and tuple(t.shape[-len(last):]) != tuple(last):
+            raise ValueError(f"{name} has shape {tuple(t.shape)}, expected trailing {tuple(last)}")
+        return t.data_ptr()
+
+    def _pinned(self, t: torch.Tensor, last, name) -> int:
+        if t.is_cuda or not t.is_pinned() or not t.is_contiguous() or t.dtype != self.torch_dtype:
+            raise ValueError(f"{name} must be a contiguous pinned host tensor of dtype {self.torch_dtype}")
+        if tuple(t.shape[-len(last):]) != tuple(last):
+            raise ValueError(f"{name} has shape {tuple(t.shape)}, expected trailing {tuple(last)}")
+        return t.data_ptr()
+
+    # -- the entry points -----------------------------------------------------------------
+    def encode_chunk(self, q, k_cache, v_cache, first_token: int, l_x: int, n_chunks: int, l_l: int,
+                     out=None):
+        qh, kh = (self.n_q_heads, self.head_dim), (self.n_kv_heads, self.head_dim)
+        if q.shape[0] != n_chunks * l_x:
+            raise ValueError("q must hold n_chunks * l_x tokens")
+        if k_cache.shape[0] < first_token + n_chunks * l_x or v_cache.shape[0] != k_cache.shape[0]:
+            raise ValueError("k_cache / v_cache are shorter than first_token + n_chunks * l_x")
+        out = torch.empty_like(q) if out is None else out
+        if out.shape != q.shape:
+            raise ValueError("out must have the shape of q")
+        self._check(self._lib.rekv_encode_chunk(
+            self._h, self._dev(q, last=qh, name="q"), self._dev(k_cache, last=kh, name="k_cache"),
+            self._dev(v_cache, last=kh, name="v_cache"), first_token, l_x, n_chunks, l_l,
+            self._dev(out, last=qh, name="out"), _stream()))
+        return out
+
+    def frame_keys(self, k, n_frames: int, out=None):
+        kh = (self.n_kv_heads, self.head_dim)
+        if k.shape[0] < n_frames * self.tokens_per_frame:
+            raise ValueError("k is shorter than n_frames * tokens_per_frame")
+        d_prime = self.n_kv_heads * self.head_dim
+        out = torch.empty((n_frames, d_prime), dtype=torch.float32, device=k.device) if out is None else out
+        if out.shape[0] < n_frames:
+            raise ValueError("frame_keys output is shorter than n_frames")
+        self._check(self._lib.rekv_frame_keys(
+            self._h, self._dev(k, last=kh, name="k"), n_frames,
+            self._dev(out, torch.float32, (d_prime,), "frame_keys"), _stream()))
+        return out
+
+    def retrieve_topk(self, frame_keys, n_frames: int, q_question, k: int, frame_keys_stride: int = 0,
+                      want_scores: bool = False):
+        """q_question [n_questions, N_q, Hq, D].  Returns (idx [n_questions, k] int32, n_sel, scores|None)."""
+        if q_question.dim() != 4:
+            raise ValueError("q_question must be [n_questions, N_q, Hq, D]")
+        nq, n_q_tokens = q_question.shape[0], q_question.shape[1]
+        d_prime = self.n_kv_heads * self.head_dim
+        tables = nq if frame_keys_stride else 1
+        need = (tables - 1) * frame_keys_stride + n_frames * d_prime
+        if frame_keys.numel() < need:
+            raise ValueError("frame_keys holds fewer elements than the tables addressed")
+        dev = q_question.device
+        idx = torch.empty((nq, k), dtype=torch.int32, device=dev)
+        n_sel = torch.empty((nq,), dtype=torch.int32, device=dev)
+        scores = torch.empty((nq, n_frames), dtype=torch.float32, device=dev) if want_scores else None
+        self._check(self._lib.rekv_retrieve_topk(
+            self._h, self._dev(frame_keys, torch.float32, name="frame_keys"), frame_keys_stride, n_frames,
+            self._dev(q_question, last=(self.n_q_heads, self.head_dim), name="q_question"), nq, n_q_tokens, k,
+            idx.data_ptr(), n_sel.data_ptr(), scores.data_ptr() if want_scores else None, _stream()))
+        return idx, n_sel, scores
+
+    def gather_kv(self, src_k, src_v, idx, n_src_frames: int | None = None, dst_k=None, dst_v=None):
+        """idx [n_questions, k] int32 on the device.  src on the device, or pinned on the host."""
+        kh = (self.n_kv_heads, self.head_dim)
+        on_host = not src_k.is_cuda
+        nf = src_k.shape[0] // self.tokens_per_frame if n_src_frames is None else n_src_frames
+        if src_k.shape[0] < nf * self.tokens_per_frame or src_v.shape != src_k.shape:
+            raise ValueError("src_k / src_v are shorter than n_src_frames frames")
+        if idx.dim() != 2 or idx.dtype != torch.int32:
+            raise ValueError("idx must be [n_questions, k] int32")
+        nq, k = idx.shape
+        shape = (nq, k * self.tokens_per_frame, *kh)
+        dst_k = torch.empty(shape, dtype=self.torch_dtype, device=idx.device) if dst_k is None else dst_k
+        dst_v = torch.empty(shape, dtype=self.torch_dtype, device=idx.device) if dst_v is None else dst_v
+        if tuple(dst_k.shape) != shape or tuple(dst_v.shape) != shape:
+            raise ValueError(f"dst_k / dst_v must have shape {shape}")
+        ps = (self._pinned(src_k, kh, "src_k"), self._pinned(src_v, kh, "src_v")) if on_host else \
+             (self._dev(src_k, last=kh, name="src_k"), self._dev(src_v, last=kh, name="src_v"))
+        self._check(self._lib.rekv_gather_kv(
+            self._h, ps[0], ps[1], 1 if on_host else 0, nf, self._dev(idx, torch.int32, name="idx"), nq, k,
+            self._dev(dst_k, name="dst_k"), self._dev(dst_v, name="dst_v"), _stream()))
+        return dst_k, dst_v
+
+    def qa_attention(self, q, k_ret, v_ret, k_self, v_self, out=None):
+        """q [n_questions, N_q, Hq, D]; k_ret/v_ret [n_questions, n_ret, Hkv, D]; k_self/v_self
+        [n_questions, N_q, Hkv, D]."""
+        qh, kh = (self.n_q_heads, self.head_dim), (self.n_kv_heads, self.head_dim)
+        if q.dim() != 4 or k_ret.dim() != 4 or k_self.dim() != 4:
+            raise ValueError("q, k_ret, k_self must be 4-d with a leading question dimension")
+        nq, n_q_tokens = q.shape[0], q.shape[1]
+        n_ret = k_ret.shape[1]
+        if k_ret.shape[0] != nq or v_ret.shape != k_ret.shape:
+            raise ValueError("k_ret / v_ret must be [n_questions, n_ret, Hkv, D]")
+        if tuple(k_self.shape[:2]) != (nq, n_q_tokens) or v_self.shape != k_self.shape:
+            raise ValueError("k_self / v_self must be [n_questions, N_q, Hkv, D]")
+        out = torch.empty_like(q) if out is None else out
+        if out.shape != q.shape:
+            raise ValueError("out must have the shape of q")
+        self._check(self._lib.rekv_qa_attention(
+            self._h, self._dev(q, last=qh, name="q"),
+            self._dev(k_ret, last=kh, name="k_ret") if n_ret else None,
+            self._dev(v_ret, last=kh, name="v_ret") if n_ret else None, n_ret,
+            self._dev(k_self, last=kh, name="k_self"), self._dev(v_self, last=kh, name="v_self"),
+            nq, n_q_tokens, self._dev(out, last=qh, name="out"), _stream()))
+        return out
+
+    def offload_kv(self, dev_k, dev_v, host_k, host_v, first_frame: int, n_frames: int):
+        kh = (self.n_kv_heads, self.head_dim)
+        need = (first_frame + n_frames) * self.tokens_per_frame
+        if min(dev_k.shape[0], dev_v.shape[0], host_k.shape[0], host_v.shape[0]) < need:
+            raise ValueError("a K/V array is shorter than first_frame + n_frames frames")
+        self._check(self._lib.rekv_offload_kv(
+            self._h, self._dev(dev_k, last=kh, name="dev_k"), self._dev(dev_v, last=kh, name="dev_v"),
+            self._pinned(host_k, kh, "host_k"), self._pinned(host_v, kh, "host_v"), first_frame, n_frames,
+            _stream()))
+
+    def offload_wait(self):
+        self._check(self._lib.rekv_offload_wait(self._h))

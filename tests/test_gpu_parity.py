@@ -1,0 +1,338 @@
+"""HIP path vs the CPU oracle, element by element, on the same seeded inputs.  Everything
+here goes through the C ABI (via the ctypes binding) and needs a real MI355X.
+
+Tolerances (from the benchmark definition): attention outputs max-abs 2e-2 for bf16
+inputs and 1e-4 for fp32 inputs; frame vectors and scores 1e-5 (fp32 sums of O(1) values);
+top-k indices bit-exact wherever the k-th and (k+1)-th scores differ by more than 1e-3;
+gather bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rekv_oracle as O
+from paper_2503_00540_amd import workloads as W
+from paper_2503_00540_amd.rekv import Rekv, RekvError
+
+pytestmark = pytest.mark.gpu
+TOL = {"bf16": 2e-2, "f32": 1e-4}
+DEV = "cuda:0"
+
+
+def dev(x, w):
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    return t.to(torch.bfloat16 if w.dtype == "bf16" else torch.float32).to(DEV)
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def check_topk(idx_gpu, scores_oracle, k):
+    """GPU selection vs the oracle's scores under the stated rule: exact where the k-th and
+    (k+1)-th scores are more than 1e-3 apart; otherwise everything clearly above the cut is
+    in, nothing clearly below it is."""
+    F = len(scores_oracle)
+    ref = O.topk_frames(scores_oracle, k)
+    got = np.asarray(idx_gpu)
+    n = min(k, F)
+    assert (got[n:] == -1).all()
+    got = got[:n]
+    assert (np.diff(got) > 0).all()                     # ascending, hence distinct
+    if n == F:
+        np.testing.assert_array_equal(got, np.arange(F))
+        return
+    srt = np.sort(scores_oracle)[::-1]
+    if srt[n - 1] - srt[n] > 1e-3:
+        np.testing.assert_array_equal(got, ref)
+    else:
+        cut = srt[n - 1]
+        assert set(np.nonzero(scores_oracle > cut + 1e-3)[0]) <= set(got)
+        assert not (set(np.nonzero(scores_oracle < cut - 1e-3)[0]) & set(got))
+
+
+# ----------------------------------------------------------------------------------------
+# C0: the whole tiny fp32 stream, every step of the path
+# ----------------------------------------------------------------------------------------
+def test_c0_whole_path_fp32():
+    w = W.C0
+    q, k, v = W.frames_q(w, 0, w.n_frames), W.frames_k(w, 0, w.n_frames), W.frames_v(w, 0, w.n_frames)
+    r = Rekv.for_workload(w)
+    dq, dk, dv = dev(q, w), dev(k, w), dev(v, w)
+    n_chunks = w.n_frames // w.chunk_frames
+    out = r.encode_chunk(dq, dk, dv, 0, w.l_x, n_chunks, w.l_l)
+    ref = O.encode_chunks(q, k, v, 0, w.l_x, n_chunks, w.l_l)
+    assert np.abs(host(out) - ref).max() < TOL["f32"]
+    # chunk by chunk gives the same as one call
+    out2 = torch.cat([r.encode_chunk(dq[c * w.l_x:(c + 1) * w.l_x], dk, dv, c * w.l_x, w.l_x, 1, w.l_l)
+                      for c in range(n_chunks)])
+    assert torch.equal(out, out2)
+
+    fk = r.frame_keys(dk, w.n_frames)
+    fk_ref = O.frame_keys(k, w.n_frames, w.tokens_per_frame)
+    assert np.abs(host(fk) - fk_ref).max() < 1e-5
+
+    qq, qk, qv = W.question_qkv(w)
+    idx, n_sel, scores = r.retrieve_topk(fk, w.n_frames, dev(qq, w)[None], w.top_k, want_scores=True)
+    ref_idx, ref_s = O.retrieve(fk_ref, qq, w.n_kv_heads, w.top_k)
+    assert np.abs(host(scores)[0] - ref_s).max() < 1e-5
+    assert int(n_sel[0]) == w.top_k
+    check_topk(idx[0].cpu().numpy(), ref_s, w.top_k)
+    assert int(scores[0].argmax()) == 7 and 7 in idx[0].tolist()      # the planted frame
+
+    gk, gv = r.gather_kv(dk, dv, idx)
+    rk, rv = O.gather_kv(k, v, ref_idx, w.tokens_per_frame)
+    assert gk.shape == (1, 64, 1, 64)
+    assert host(gk)[0].tobytes() == rk.astype(np.float64).tobytes()
+    assert host(gv)[0].tobytes() == rv.astype(np.float64).tobytes()
+
+    o = r.qa_attention(dev(qq, w)[None], gk, gv, dev(qk, w)[None], dev(qv, w)[None])
+    o_ref = O.qa_attention(qq, rk, rv, qk, qv)
+    assert np.abs(host(o)[0] - o_ref).max() < TOL["f32"]
+
+
+# ----------------------------------------------------------------------------------------
+# encode, Eq. 1
+# ----------------------------------------------------------------------------------------
+ENCODE_CASES = [
+    # name, workload, n_frames, chunk_frames, window_frames(None = tokens below), l_l tokens, chunks to check
+    ("7B-ragged", W.C1, 20, 1, 16, None, [0, 1, 15, 16, 19]),
+    ("7B-window-not-tile-multiple", W.C1, 6, 1, None, 250, [0, 2, 5]),
+    ("7B-no-window", W.C1, 3, 1, None, 0, [0, 2]),
+    ("7B-chunk-of-4-frames", W.C1, 12, 4, None, 1000, [0, 1, 2]),
+    ("0.5B-D64", W.C1.scaled(n_q_heads=14, n_kv_heads=2, head_dim=64, name="C1-0.5B"), 8, 1, 4, None, [0, 3, 4, 7]),
+    ("72B-G8", W.C4, 6, 1, 4, None, [0, 4, 5]),
+    ("f32-D64-ragged", W.C0.scaled(tokens_per_frame=37, n_q_heads=6, n_kv_heads=2, name="C0r"), 9, 1, None, 100, [0, 3, 8]),
+    ("f32-D128", W.C0.scaled(head_dim=128, tokens_per_frame=20, name="C0d"), 6, 2, None, 50, [0, 1, 2]),
+]
+
+
+@pytest.mark.parametrize("case", ENCODE_CASES, ids=[c[0] for c in ENCODE_CASES])
+def test_encode_matches_oracle(case):
+    _, w0, n_frames, chunk_frames, win_frames, l_l, chunks = case
+    w = w0.scaled(n_frames=n_frames, chunk_frames=chunk_frames)
+    l_l = win_frames * w.tokens_per_frame if l_l is None else l_l
+    q, k, v = W.frames_q(w, 0, n_frames), W.frames_k(w, 0, n_frames), W.frames_v(w, 0, n_frames)
+    r = Rekv.for_workload(w)
+    n_chunks = n_frames // chunk_frames
+    dq, dk, dv = dev(q, w), dev(k, w), dev(v, w)
+    out = host(r.encode_chunk(dq, dk, dv, 0, w.l_x, n_chunks, l_l))
+    assert np.isfinite(out).all()
+    for c in chunks:
+        sl = slice(c * w.l_x, (c + 1) * w.l_x)
+        ref = O.encode_chunks(q[sl], k, v, c * w.l_x, w.l_x, 1, l_l)
+        err = np.abs(out[sl] - ref).max()
+        assert err < TOL[w.dtype], (c, err)
+        # one chunk per call: few workgroups, so the key range is split over several of
+        # them and merged - must agree with the oracle as well
+        one = host(r.encode_chunk(dq[sl], dk, dv, c * w.l_x, w.l_x, 1, l_l))
+        err = np.abs(one - ref).max()
+        assert err < TOL[w.dtype], ("single", c, err)
+
+
+def test_encode_single_token_chunks_and_custom_scale():
+    """l_x = 1 (a chunk is one token) and a caller-given softmax scale."""
+    w = W.C1.scaled(n_frames=3)
+    q, k, v = W.frames_q(w, 0, 3), W.frames_k(w, 0, 3), W.frames_v(w, 0, 3)
+    r = Rekv.for_workload(w, softmax_scale=0.05)
+    T = 3 * w.tokens_per_frame
+    out = host(r.encode_chunk(dev(q, w)[400:], dev(k, w), dev(v, w), 400, 1, T - 400, 300))
+    ref = O.encode_chunks(q[400:], k, v, 400, 1, T - 400, 300, scale=0.05)
+    assert np.abs(out - ref).max() < TOL["bf16"]
+
+
+def test_encode_rejects_bad_arguments():
+    w = W.C1.scaled(n_frames=2)
+    r = Rekv.for_workload(w)
+    q, k = dev(W.frames_q(w, 0, 1), w), dev(W.frames_k(w, 0, 2), w)
+    with pytest.raises(RekvError, match="INVALID_ARG"):
+        r._check(r._lib.rekv_encode_chunk(r._h, q.data_ptr(), k.data_ptr(), k.data_ptr(), 0, 0, 1, 0,
+                                          q.data_ptr(), None))
+    with pytest.raises(RekvError, match="INVALID_ARG"):
+        r._check(r._lib.rekv_encode_chunk(r._h, q.data_ptr(), None, k.data_ptr(), 0, 196, 1, 0,
+                                          q.data_ptr(), None))
+    with pytest.raises(RekvError, match="aligned"):
+        r._check(r._lib.rekv_encode_chunk(r._h, q.data_ptr() + 2, k.data_ptr(), k.data_ptr(), 0, 195, 1, 0,
+                                          q.data_ptr(), None))
+    with pytest.raises(ValueError):
+        r.encode_chunk(q, k, k, 196, 196, 2, 0)        # cache too short for two chunks
+
+
+# ----------------------------------------------------------------------------------------
+# frame vectors, scores, top-k
+# ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("w", [W.C1.scaled(n_frames=37), W.C4.scaled(n_frames=21),
+                               W.C1.scaled(n_q_heads=14, n_kv_heads=2, head_dim=64, n_frames=9, name="0.5B"),
+                               W.C0.scaled(tokens_per_frame=5, n_frames=11, name="C0r")],
+                         ids=["7B", "72B", "0.5B", "f32"])
+def test_frame_keys_match_oracle(w):
+    k = W.frames_k(w, 0, w.n_frames)
+    r = Rekv.for_workload(w)
+    fk = host(r.frame_keys(dev(k, w), w.n_frames))
+    assert np.abs(fk - O.frame_keys(k, w.n_frames, w.tokens_per_frame)).max() < 1e-5
+    # a prefix of the frames
+    fk3 = host(r.frame_keys(dev(k, w), 3))
+    np.testing.assert_array_equal(fk3, fk[:3])
+
+
+@pytest.mark.parametrize("w,nq", [(W.C1.scaled(n_frames=300), 1), (W.C4.scaled(n_frames=130), 19),
+                                  (W.C2.scaled(n_frames=1000), 3)], ids=["7B", "72B-19q", "hour-64"])
+def test_retrieval_matches_oracle(w, nq):
+    k = W.frames_k(w, 0, w.n_frames)
+    fk_ref = O.frame_keys(k, w.n_frames, w.tokens_per_frame)
+    r = Rekv.for_workload(w)
+    fk = r.frame_keys(dev(k, w), w.n_frames)
+    qs = [W.question_qkv(w, i)[0] for i in range(nq)]
+    dq = dev(np.stack(qs), w)
+    n_vis = w.n_frames - 7                              # the question's timestamp hides 7 frames
+    idx, n_sel, scores = r.retrieve_topk(fk, n_vis, dq, w.top_k, want_scores=True)
+    idx2, _, none = r.retrieve_topk(fk, n_vis, dq, w.top_k)            # scores kept internal
+    assert none is None and torch.equal(idx, idx2)
+    for i in range(nq):
+        ref_idx, ref_s = O.retrieve(fk_ref, qs[i], w.n_kv_heads, w.top_k, n_visible=n_vis)
+        assert np.abs(host(scores)[i] - ref_s).max() < 1e-5
+        check_topk(idx[i].cpu().numpy(), ref_s, w.top_k)
+        # the selection itself is exact given the scores it saw (ties to the lower index)
+        np.testing.assert_array_equal(idx[i].cpu().numpy(), O.topk_frames(host(scores)[i], w.top_k))
+        planted = [p for p in W.planted_frames(w, i) if p < n_vis]
+        assert set(planted) <= set(idx[i].tolist())
+        assert int(n_sel[i]) == w.top_k
+
+
+def test_per_layer_tables_retrieve_independently():
+    """Each 'question' row has its own frame-key table (one per layer)."""
+    w = W.C3.scaled(n_frames=40, n_layers=3)
+    r = Rekv.for_workload(w)
+    fks, qs, refs = [], [], []
+    for layer in range(3):
+        k = W.frames_k(w, 0, w.n_frames, layer)
+        fks.append(r.frame_keys(dev(k, w), w.n_frames))
+        qq = W.question_qkv(w, 0, layer)[0]
+        qs.append(qq)
+        refs.append(O.retrieve(O.frame_keys(k, w.n_frames, w.tokens_per_frame), qq, w.n_kv_heads, w.top_k))
+    table = torch.stack(fks)                                        # [layers, F, D']
+    idx, _, scores = r.retrieve_topk(table, w.n_frames, dev(np.stack(qs), w), w.top_k,
+                                     frame_keys_stride=w.n_frames * w.d_prime, want_scores=True)
+    for layer in range(3):
+        assert np.abs(host(scores)[layer] - refs[layer][1]).max() < 1e-5
+        check_topk(idx[layer].cpu().numpy(), refs[layer][1], w.top_k)
+    assert not torch.equal(idx[0], idx[1])
+
+
+def test_topk_ties_and_degenerate_sizes():
+    w = W.C0.scaled(n_frames=300, tokens_per_frame=2, name="ties")
+    r = Rekv.for_workload(w)
+    k = W.frames_k(w, 0, w.n_frames)
+    k[40:] = np.tile(k[:40], (15, 1, 1))[: len(k) - 40]     # frames repeat with period 20: exact ties
+    fk = r.frame_keys(dev(k, w), w.n_frames)
+    qq = W.question_qkv(w)[0]
+    for kk in (1, 2, 15, 16, 17, 64, 299, 300, 301, 500):
+        idx, n_sel, scores = r.retrieve_topk(fk, w.n_frames, dev(qq, w)[None], kk, want_scores=True)
+        s = host(scores)[0]
+        assert len(np.unique(s)) <= 21
+        ref = O.topk_frames(s, kk)
+        got = idx[0].cpu().numpy()
+        np.testing.assert_array_equal(got[: len(ref)], ref)
+        assert (got[len(ref):] == -1).all() and int(n_sel[0]) == min(kk, 300)
+    # zero keys and a zero question score 0 everywhere: the first k frames win
+    z = torch.zeros_like(fk)
+    idx, _, scores = r.retrieve_topk(z, 300, dev(qq, w)[None], 5, want_scores=True)
+    assert idx[0].tolist() == [0, 1, 2, 3, 4] and float(scores.abs().max()) == 0.0
+    # a single visible frame
+    idx, n_sel, _ = r.retrieve_topk(fk, 1, dev(qq, w)[None], 4)
+    assert idx[0].tolist() == [0, -1, -1, -1] and int(n_sel[0]) == 1
+    with pytest.raises(RekvError, match="INVALID_ARG"):
+        r.retrieve_topk(fk, 300, dev(qq, w)[None], 0)
+
+
+# ----------------------------------------------------------------------------------------
+# gather (device and pinned-host source), offload
+# ----------------------------------------------------------------------------------------
+def test_gather_device_and_host_bit_exact():
+    w = W.C1.scaled(n_frames=24)
+    r = Rekv.for_workload(w)
+    k, v = W.frames_k(w, 0, w.n_frames), W.frames_v(w, 0, w.n_frames)
+    dk, dv = dev(k, w), dev(v, w)
+    sel = np.array([[0, 3, 4, 5, 23], [1, 2, 9, -1, -1]], dtype=np.int32)
+    idx = torch.from_numpy(sel).to(DEV)
+    gk, gv = r.gather_kv(dk, dv, idx)
+    hk = torch.empty(dk.shape, dtype=dk.dtype, pin_memory=True)
+    hv = torch.empty(dv.shape, dtype=dv.dtype, pin_memory=True)
+    r.offload_kv(dk, dv, hk, hv, 0, 10)                  # offload in two pieces
+    r.offload_kv(dk, dv, hk, hv, 10, 14)
+    r.offload_wait()
+    assert torch.equal(hk, dk.cpu()) and torch.equal(hv, dv.cpu())
+    gk_h, gv_h = r.gather_kv(hk, hv, idx)
+    torch.cuda.synchronize()
+    assert torch.equal(gk, gk_h) and torch.equal(gv, gv_h)
+    nf = w.tokens_per_frame
+    for qi in range(2):
+        frames = [f for f in sel[qi] if f >= 0]
+        rk, rv = O.gather_kv(k, v, frames, nf)
+        n = len(frames) * nf
+        assert host(gk)[qi, :n].tobytes() == rk.astype(np.float64).tobytes()
+        assert host(gv)[qi, :n].tobytes() == rv.astype(np.float64).tobytes()
+        assert float(gk[qi, n:].abs().max() if n < gk.shape[1] else 0) == 0     # skipped slots are zero
+    bad = torch.tensor([[0, 99]], dtype=torch.int32, device=DEV)
+    with pytest.raises(RekvError, match="INVALID_ARG"):
+        r.gather_kv(hk, hv, bad)
+
+
+# ----------------------------------------------------------------------------------------
+# QA attention, Eq. 3
+# ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("w,nq,n_ret_frames", [
+    (W.C1, 1, 16), (W.C1, 3, 5), (W.C1, 2, 0), (W.C4.scaled(n_q_tokens=17), 5, 3),
+    (W.C2, 1, 64), (W.C0.scaled(tokens_per_frame=7, name="C0q"), 2, 3)],
+    ids=["7B-k16", "7B-3q-k5", "no-retrieved", "72B-5q-ragged", "hour-k64", "f32"])
+def test_qa_attention_matches_oracle(w, nq, n_ret_frames):
+    w = w.scaled(n_frames=max(2 * n_ret_frames, 4))
+    r = Rekv.for_workload(w)
+    k, v = W.frames_k(w, 0, w.n_frames), W.frames_v(w, 0, w.n_frames)
+    nf = w.tokens_per_frame
+    qs, ks, vs, rks, rvs = [], [], [], [], []
+    for i in range(nq):
+        qq, qk, qv = W.question_qkv(w, i)
+        frames = list(range(i % 2, i % 2 + n_ret_frames))
+        rk, rv = O.gather_kv(k, v, frames, nf)
+        qs.append(qq); ks.append(qk); vs.append(qv); rks.append(rk); rvs.append(rv)
+    shape_ret = (nq, n_ret_frames * nf, w.n_kv_heads, w.head_dim)
+    out = r.qa_attention(dev(np.stack(qs), w), dev(np.stack(rks).reshape(shape_ret), w),
+                         dev(np.stack(rvs).reshape(shape_ret), w), dev(np.stack(ks), w), dev(np.stack(vs), w))
+    out = host(out)
+    for i in range(nq):
+        ref = O.qa_attention(qs[i], rks[i], rvs[i], ks[i], vs[i])
+        err = np.abs(out[i] - ref).max()
+        assert err < TOL[w.dtype], (i, err)
+
+
+# ----------------------------------------------------------------------------------------
+# the benchmark's launch configuration at full size, on sampled chunks
+# ----------------------------------------------------------------------------------------
+def test_c1_full_size_sampled_chunks_and_retrieval():
+    w = W.C1
+    n_chunks = w.n_frames // w.chunk_frames
+    q, k, v = W.frames_q(w, 0, w.n_frames), W.frames_k(w, 0, w.n_frames), W.frames_v(w, 0, w.n_frames)
+    r = Rekv.for_workload(w)
+    dq, dk, dv = dev(q, w), dev(k, w), dev(v, w)
+    out = r.encode_chunk(dq, dk, dv, 0, w.l_x, n_chunks, w.l_l)      # one call, as bench.py times it
+    torch.cuda.synchronize()
+    for c in W.parity_chunks(n_chunks, w.window_frames):
+        sl = slice(c * w.l_x, (c + 1) * w.l_x)
+        ref = O.encode_chunks(q[sl], k, v, c * w.l_x, w.l_x, 1, w.l_l)
+        err = np.abs(host(out[sl]) - ref).max()
+        assert err < TOL["bf16"], (c, err)
+    fk = r.frame_keys(dk, w.n_frames)
+    fk_ref = O.frame_keys(k, w.n_frames, w.tokens_per_frame)
+    assert np.abs(host(fk) - fk_ref).max() < 1e-5
+    qq, qk, qv = W.question_qkv(w)
+    idx, _, scores = r.retrieve_topk(fk, w.n_frames, dev(qq, w)[None], w.top_k, want_scores=True)
+    ref_idx, ref_s = O.retrieve(fk_ref, qq, w.n_kv_heads, w.top_k)
+    check_topk(idx[0].cpu().numpy(), ref_s, w.top_k)
+    assert set(W.planted_frames(w)) <= set(idx[0].tolist())
+    gk, gv = r.gather_kv(dk, dv, idx)
+    o = r.qa_attention(dev(qq, w)[None], gk, gv, dev(qk, w)[None], dev(qv, w)[None])
+    rk, rv = O.gather_kv(k, v, idx[0].tolist(), w.tokens_per_frame)
+    assert host(gk)[0].tobytes() == rk.astype(np.float64).tobytes()
+    o_ref = O.qa_attention(qq, rk, rv, qk, qv)
+    assert np.abs(host(o)[0] - o_ref).max() < TOL["bf16"]
