@@ -18,7 +18,7 @@ SOURCES = ["api.hip", "attention_bf16.hip", "attention_f32.hip", "retrieval.hip"
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wno-unused-command-line-argument",
+    "-Wno-unused-command-line-argument", "-Wno-inline-asm",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 

@@ -4,7 +4,7 @@
 // Work split.  A workgroup of 4 wavefronts owns BM = 128 query rows of one (item, KV head):
 // the G = Hq / Hkv query heads that share the KV head are stacked into the row dimension
 // (row = token * G + head-in-group), so one K/V tile staged in LDS serves all of them.
-// The key range (segment A unmasked, then segment B causal) is walked in tiles of 64 keys;
+// The key range (segment A unmasked, then segment B causal) is walked in tiles of 32 keys;
 // optionally several workgroups split the tile list (split-KV) and a merge kernel combines
 // their (max, sum, unnormalised O) partial results.
 //
@@ -12,13 +12,31 @@
 // that a query is an MFMA column: it lives in one lane (and its partner lane + 32), softmax
 // statistics need no cross-lane traffic beyond one exchange with that partner, and the
 // S^T accumulator registers are, after packing to bf16, exactly the B operand of the PV
-// product.  V is transposed on its way into LDS so that its A operand is one 16-byte read.
+// product.
+//
+// Data movement.  K and V tiles go from global memory straight into LDS (global_load_lds,
+// 16 bytes per lane, no staging registers), row-major [key][D] with the 16-byte chunks of a
+// row XOR-swizzled by the key index so that neither the K operand reads (ds_read_b128, 16
+// consecutive keys per quarter-wave) nor the V operand reads hit a bank twice.  The V^T
+// operand is read with ds_read_b64_tr_b16, which transposes 4 keys x 16 dims among 16 lanes.
+//
+// Pipeline.  Tiles are 32 keys; per tile t one barrier.  While the softmax of tile t runs on
+// the vector ALU, the matrix cores compute S^T of tile t+1 and the PV product of tile t;
+// K(t+4) and V(t+3) are being fetched, so a load has three steps to land.  The four K and
+// four V stages are eight distinct arrays and the loop is unrolled by four, so every LDS
+// access names its array (the compiler then orders reads only against loads into the same
+// array).  Every step issues the same number of loads per wave (past the end of the tile
+// list the last tile is fetched again into a stage nobody reads), so "all but the newest
+// N loads have landed" is one s_waitcnt vmcnt(N).
+#include <type_traits>
+
 #include "common.h"
 
 namespace rekv {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -26,7 +44,11 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int BN = 64;        // keys per tile
+#define LDS_AS __attribute__((address_space(3)))
+#define GLOBAL_AS __attribute__((address_space(1)))
+
+constexpr int BN = 32;        // keys per tile (one MFMA row block of S^T)
+constexpr int STAGES = 4;     // LDS stages per tensor
 constexpr int WAVES = 4;
 constexpr int WM = 32;        // query rows per wavefront (one MFMA column block)
 constexpr int BM = WAVES * WM;
@@ -34,15 +56,20 @@ constexpr int THREADS = WAVES * 64;
 constexpr float RESCALE_GAP = 8.0f;  // log2 units the running max may lag before O is rescaled
 
 template <int D>
-struct Tile {
-    static constexpr int KP = D + 8;    // K tile row pitch in elements: 16 B of padding
-    static constexpr int VP = BN + 8;   // V^T tile row pitch
-    static constexpr int K_ELEMS = BN * KP;
-    static constexpr int V_ELEMS = D * VP;
-    static constexpr int STAGE = K_ELEMS + V_ELEMS;
-    static constexpr int K_LOADS = BN * (D / 8) / THREADS;  // 16-byte loads per thread
-    static constexpr size_t LDS_BYTES = 2 * STAGE * sizeof(bf16_t);
+struct Cfg {
+    static constexpr int CH = D / 8;                 // 16-byte chunks per key row
+    static constexpr int RPI = 64 / CH;              // key rows one 1 KB wave-wide load covers
+    static constexpr int N_DMA = BN / RPI;           // such loads per tile and tensor
+    static constexpr int DMA_PER_WAVE = N_DMA / WAVES;
+    static constexpr int TILE_ELEMS = BN * D;
 };
+
+// Swizzle of the chunk index inside a key row: the two 2-bit fields of (key mod 16) swapped.
+// 16 consecutive keys get 16 different values; 4 consecutive keys differ in the upper field.
+template <int D>
+__device__ inline int swz(int key) {
+    return (((key & 3) << 2) | ((key >> 2) & 3)) & (Cfg<D>::CH - 1);
+}
 
 struct KernelArgs {
     AttnProblem p;
@@ -58,74 +85,55 @@ __device__ inline int xcd_remap(int bid, int nb) {
     return x * per + (x < rem ? x : rem) + (bid >> 3);
 }
 
-template <int D>
-struct Staged {
-    u32x4 k[Tile<D>::K_LOADS];
-    u32x4 v[4];
-};
+__device__ inline void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
-template <int D>
-__device__ inline void load_tile(Staged<D>& st, const bf16_t* kseg, const bf16_t* vseg,
-                                 int key0, int seg_len, int64_t row_stride, int tid) {
-    constexpr int CH = D / 8;
-#pragma unroll
-    for (int i = 0; i < Tile<D>::K_LOADS; ++i) {
-        const int id = tid + THREADS * i;
-        const int key = id / CH, c = id % CH;
-        u32x4 val = {0u, 0u, 0u, 0u};
-        if (key0 + key < seg_len)
-            val = *reinterpret_cast<const u32x4*>(kseg + (int64_t)(key0 + key) * row_stride + c * 8);
-        st.k[i] = val;
-    }
-    const int r = tid & 15, c = tid >> 4;
-    if (c < CH) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int key = key0 + 4 * r + i;
-            u32x4 val = {0u, 0u, 0u, 0u};
-            if (key < seg_len)
-                val = *reinterpret_cast<const u32x4*>(vseg + (int64_t)key * row_stride + c * 8);
-            st.v[i] = val;
-        }
-    }
+// End of a pipeline step: this wave's loads except the newest N have landed, its LDS reads
+// have returned, then the workgroup barrier.  No fence: a fence would drain the newest loads.
+// One 16-byte-per-lane load from global memory straight into LDS: lane i's 16 bytes land at
+// lds_addr + 16 * i.  Written as asm so that the loads stay invisible to the compiler's
+// wait-count bookkeeping: with more than a handful of such loads in a loop it would drain
+// all of them before any LDS read.  Ordering is explicit instead (step_barrier).
+// The source address is a wave-uniform base plus a 32-bit per-lane byte offset.
+__device__ inline void dma16(const void* base, uint32_t lane_off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 ::"v"(lane_off), "s"(base), "s"(__builtin_amdgcn_readfirstlane(lds_addr)) : "memory", "m0");
+}
+__device__ inline uint32_t lds_addr_of(const void* p) {
+    return (uint32_t)(uintptr_t)(LDS_AS const void*)p;
+}
+
+// A query's two lanes (lane, lane ^ 32) combine a value without touching LDS:
+// v_permlane32_swap hands every lane both halves' values.
+__device__ inline float pair_max(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float pair_sum(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+template <int N>
+__device__ inline void step_barrier() {
+    static_assert(N >= 0 && N < 16, "vmcnt immediate");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
 template <int D>
-__device__ inline void store_tile(const Staged<D>& st, bf16_t* kl, bf16_t* vl, int tid) {
-    constexpr int CH = D / 8;
-#pragma unroll
-    for (int i = 0; i < Tile<D>::K_LOADS; ++i) {
-        const int id = tid + THREADS * i;
-        const int key = id / CH, c = id % CH;
-        *reinterpret_cast<u32x4*>(kl + key * Tile<D>::KP + c * 8) = st.k[i];
-    }
-    // V^T: thread (r, c) holds keys 4r..4r+3 x dims 8c..8c+7.  Inside each group of 16 keys the
-    // quads are stored in the order 0,2,1,3, which is the order the PV product's k-slots take
-    // them from the S^T accumulator registers.
-    const int r = tid & 15, c = tid >> 4;
-    if (c < CH) {
-        const int q = r & 3;
-        const int pos = (r >> 2) * 16 + (((q & 1) << 1) | (q >> 1)) * 4;
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {
-            const uint32_t a = st.v[0][e2], b = st.v[1][e2], c2 = st.v[2][e2], d2 = st.v[3][e2];
-            u32x2 lo, hi;
-            lo.x = __builtin_amdgcn_perm(b, a, 0x05040100u);   // (a.lo, b.lo)
-            lo.y = __builtin_amdgcn_perm(d2, c2, 0x05040100u);
-            hi.x = __builtin_amdgcn_perm(b, a, 0x07060302u);   // (a.hi, b.hi)
-            hi.y = __builtin_amdgcn_perm(d2, c2, 0x07060302u);
-            *reinterpret_cast<u32x2*>(vl + (c * 8 + 2 * e2) * Tile<D>::VP + pos) = lo;
-            *reinterpret_cast<u32x2*>(vl + (c * 8 + 2 * e2 + 1) * Tile<D>::VP + pos) = hi;
-        }
-    }
-}
+__global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
+    typedef Cfg<D> C;
+    __shared__ __attribute__((aligned(1024))) bf16_t ks0[C::TILE_ELEMS];
+    __shared__ __attribute__((aligned(1024))) bf16_t ks1[C::TILE_ELEMS];
+    __shared__ __attribute__((aligned(1024))) bf16_t ks2[C::TILE_ELEMS];
+    __shared__ __attribute__((aligned(1024))) bf16_t ks3[C::TILE_ELEMS];
+    __shared__ __attribute__((aligned(1024))) bf16_t vs0[C::TILE_ELEMS];
+    __shared__ __attribute__((aligned(1024))) bf16_t vs1[C::TILE_ELEMS];
+    __shared__ __attribute__((aligned(1024))) bf16_t vs2[C::TILE_ELEMS];
+    __shared__ __attribute__((aligned(1024))) bf16_t vs3[C::TILE_ELEMS];
 
-template <int D>
-__global__ __launch_bounds__(THREADS) void attn_bf16_kernel(KernelArgs a) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
     const AttnProblem& p = a.p;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hh = lane >> 5;
     const int G = p.n_q_heads / p.n_kv_heads;
 
@@ -160,6 +168,65 @@ __global__ __launch_bounds__(THREADS) void attn_bf16_kernel(KernelArgs a) {
     int t_end = t_begin + per_split;
     if (t_end > n_tiles) t_end = n_tiles;
 
+    // ---- lane-constant addressing -----------------------------------------------------
+    // global -> LDS: load j of this wave fills LDS rows dma_row + j*RPI, chunk slot dma_p
+    const int dma_row = wave * C::DMA_PER_WAVE * C::RPI + lane / C::CH;
+    const int dma_p = lane % C::CH;
+    int dma_coff[C::DMA_PER_WAVE];               // element offset of the chunk to fetch
+#pragma unroll
+    for (int j = 0; j < C::DMA_PER_WAVE; ++j)
+        dma_coff[j] = (dma_p ^ swz<D>(dma_row + j * C::RPI)) * 8;
+    // K operand (A of S^T = K Q^T): key row col, dims ks*16 + hh*8 .. +8
+    int k_off[D / 16];
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) k_off[ks] = col * D + (((ks * 2 + hh) ^ swz<D>(col)) * 8);
+    // V^T operand (A of O^T = V^T P^T) through the transposing read: this lane supplies the
+    // address of 4 dims of one key; which key and dims follows from the lane's place in its
+    // group of 16.  r picks the first or second set of 4 k-slots of the MFMA.
+    int v_off[2][D / 32];
+    {
+        const int gq = lane >> 4, i16 = lane & 15, qd = i16 & 3, jk = i16 >> 2;
+        const int cl = (gq & 1) * 2 + (qd >> 1), half = qd & 1;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int keyl = r * 8 + hh * 4 + jk;
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+                v_off[r][db] = keyl * D + (((db * 4 + cl) ^ swz<D>(keyl)) * 8) + half * 4;
+        }
+    }
+
+    // Fetches tile t (clamped to the last tile of this workgroup's list) of K and V.  In a full
+    // tile the per-lane byte offsets are constants; only a segment's ragged last tile
+    // recomputes them, re-reading the segment's last key for the rows past its end.
+    const uint32_t row_stride_b = (uint32_t)row_stride * 2u;
+    uint32_t dma_off[C::DMA_PER_WAVE];
+#pragma unroll
+    for (int j = 0; j < C::DMA_PER_WAVE; ++j)
+        dma_off[j] = (uint32_t)(dma_row + j * C::RPI) * row_stride_b + (uint32_t)dma_coff[j] * 2u;
+    auto dma_tile = [&](int t, const bf16_t* seg_a, const bf16_t* seg_b, bf16_t* dst) {
+        t = t < t_end - 1 ? t : t_end - 1;
+        const bool in_b = t >= tiles_a;
+        const int key0 = (in_b ? t - tiles_a : t) * BN;
+        const int n_valid = (in_b ? p.len_b : seg.len_a) - key0;
+        const char* base = reinterpret_cast<const char*>(in_b ? seg_b : seg_a) + (int64_t)key0 * row_stride_b;
+        const uint32_t l = lds_addr_of(dst) + (uint32_t)(wave * C::DMA_PER_WAVE) * 1024u;
+        if (n_valid >= BN) {
+#pragma unroll
+            for (int j = 0; j < C::DMA_PER_WAVE; ++j) dma16(base, dma_off[j], l + j * 1024u);
+        } else {
+#pragma unroll
+            for (int j = 0; j < C::DMA_PER_WAVE; ++j) {
+                int r = dma_row + j * C::RPI;
+                r = r < n_valid - 1 ? r : n_valid - 1;
+                dma16(base, (uint32_t)r * row_stride_b + (uint32_t)dma_coff[j] * 2u, l + j * 1024u);
+            }
+        }
+    };
+    auto dma_k = [&](int t, bf16_t* dst) { dma_tile(t, ka, kb, dst); };
+    auto dma_v = [&](int t, bf16_t* dst) { dma_tile(t, va, vb, dst); };
+    constexpr int DMA_PER_STEP = 2 * C::DMA_PER_WAVE;
+
     // Q fragments (B operand of S^T = K Q^T): lane holds row `row`, dims ks*16 + hh*8 .. +8
     bf16x8 qf[D / 16];
     {
@@ -181,56 +248,62 @@ __global__ __launch_bounds__(THREADS) void attn_bf16_kernel(KernelArgs a) {
     float m_ref = -INFINITY, l_part = 0.f;
     const float sc = p.scale * 1.4426950408889634f;
 
-    Staged<D> st;
-    auto fetch = [&](int t) {
-        if (t < tiles_a) load_tile<D>(st, ka, va, t * BN, seg.len_a, row_stride, tid);
-        else load_tile<D>(st, kb, vb, (t - tiles_a) * BN, p.len_b, row_stride, tid);
+    typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 tr4_t;
+
+    // S^T of one tile (32 keys x 32 queries) from K fragments already in registers
+    auto qk = [&](const bf16x8 (&kf)[D / 16], f32x16& s) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s[j] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks)
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], s, 0, 0, 0);
     };
-    if (t_begin < t_end) fetch(t_begin);
-    int buf = 0;
-    for (int t = t_begin; t < t_end; ++t) {
-        bf16_t* kl = lds + buf * Tile<D>::STAGE;
-        bf16_t* vl = kl + Tile<D>::K_ELEMS;
-        store_tile<D>(st, kl, vl, tid);
-        __syncthreads();
-        if (t + 1 < t_end) fetch(t + 1);
+    auto load_k = [&](const bf16_t* kt, bf16x8 (&kf)[D / 16]) {
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) kf[ks] = *reinterpret_cast<const bf16x8*>(kt + k_off[ks]);
+    };
 
-        // ---- S^T = K Q^T: two 32-key blocks x 32 queries
-        f32x16 s[2];
+    // One pipeline step for tile t.  s_cur holds S^T(t); S^T(t+1) goes to s_next.  k_next holds
+    // K(t+1), v_cur holds V(t); K(t+4) and V(t+3) are fetched into k_load / v_load, the stages
+    // whose tiles (K(t), V(t-1)) were consumed in the step before.
+    auto step = [&](int t, f32x16& s_cur, f32x16& s_next, const bf16_t* k_next, bf16_t* k_load,
+                    const bf16_t* v_cur, bf16_t* v_load) {
+        dma_k(t + 4, k_load);
+        dma_v(t + 3, v_load);
+        // All LDS operand reads of this step are issued first; the running-maximum work below
+        // covers their latency, and the MFMAs then issue back to back.
+        bf16x8 kf[D / 16];
+        load_k(k_next, kf);
+        bf16x8 vf[2][D / 32];
+        auto load_v = [&](int g16) {
 #pragma unroll
-        for (int kbk = 0; kbk < 2; ++kbk) {
-#pragma unroll
-            for (int j = 0; j < 16; ++j) s[kbk][j] = 0.f;
-            const bf16_t* kr = kl + (kbk * 32 + col) * Tile<D>::KP + hh * 8;
-#pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) {
-                const bf16x8 af = *reinterpret_cast<const bf16x8*>(kr + ks * 16);
-                s[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, qf[ks], s[kbk], 0, 0, 0);
+            for (int db = 0; db < D / 32; ++db) {
+                const tr4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                    (LDS_AS tr4_t*)(LDS_AS void*)(v_cur + g16 * 16 * D + v_off[0][db]));
+                const tr4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                    (LDS_AS tr4_t*)(LDS_AS void*)(v_cur + g16 * 16 * D + v_off[1][db]));
+                vf[g16][db] = __builtin_shufflevector(__builtin_bit_cast(bf16x4, lo),
+                                                      __builtin_bit_cast(bf16x4, hi), 0, 1, 2, 3, 4, 5, 6, 7);
             }
-        }
-
+        };
+        load_v(0);
+        __builtin_amdgcn_sched_barrier(0);
         // ---- visibility: keys [0, lim) of this tile are visible to this lane's row
         const bool in_b = t >= tiles_a;
         const int key0 = (in_b ? t - tiles_a : t) * BN;
-        int lim = (in_b ? (tok + 1 < p.len_b ? tok + 1 : p.len_b) : seg.len_a) - key0;
-        const bool need_mask = in_b || key0 + BN > seg.len_a;
-        if (need_mask) {
+        if (in_b || key0 + BN > seg.len_a) {
+            const int lim = (in_b ? (tok + 1 < p.len_b ? tok + 1 : p.len_b) : seg.len_a) - key0;
 #pragma unroll
-            for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int key = kbk * 32 + (j >> 2) * 8 + hh * 4 + (j & 3);
-                    s[kbk][j] = key < lim ? s[kbk][j] : -INFINITY;
-                }
+            for (int j = 0; j < 16; ++j) {
+                const int key = (j >> 2) * 8 + hh * 4 + (j & 3);
+                s_cur[j] = key < lim ? s_cur[j] : -INFINITY;
+            }
         }
-
-        // ---- online softmax, one query per lane pair (lane, lane ^ 32)
-        float mx = s[0][0];
+        // ---- running maximum, one query per lane pair (lane, lane ^ 32)
+        float mx = s_cur[0];
 #pragma unroll
-        for (int j = 1; j < 16; ++j) mx = fmaxf(mx, s[0][j]);
-#pragma unroll
-        for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[1][j]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        for (int j = 1; j < 16; ++j) mx = fmaxf(mx, s_cur[j]);
+        mx = pair_max(mx);
         const float mt2 = mx * sc;
         if (__builtin_amdgcn_ballot_w64(mt2 > m_ref + RESCALE_GAP) != 0) {
             const float m_new = fmaxf(m_ref, mt2);
@@ -243,42 +316,66 @@ __global__ __launch_bounds__(THREADS) void attn_bf16_kernel(KernelArgs a) {
             m_ref = m_new;
         }
         const float mr = (m_ref == -INFINITY) ? 0.f : m_ref;
-        bf16x8 pf[4];
-#pragma unroll
-        for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2) {
-                float e[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    e[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kbk][h2 * 8 + j], sc, -mr));
-                    l_part += e[j];
-                }
-                bf16x8 pk;
-#pragma unroll
-                for (int j = 0; j < 8; j += 2) {
-                    f32x2 two = {e[j], e[j + 1]};
-                    bf16x2 b2 = __builtin_convertvector(two, bf16x2);
-                    pk[j] = b2[0];
-                    pk[j + 1] = b2[1];
-                }
-                pf[kbk * 2 + h2] = pk;
-            }
 
-        // ---- O^T += V^T P^T
+        // ---- matrix cores: S^T(t+1); vector ALU: exp of tile t; then O^T += V^T P^T
+        qk(kf, s_next);            // past the last tile this works on a stale stage and is unused
+        load_v(1);
 #pragma unroll
-        for (int g16 = 0; g16 < 4; ++g16) {
-            const bf16_t* vr = vl + col * Tile<D>::VP + g16 * 16 + hh * 8;
+        for (int g16 = 0; g16 < 2; ++g16) {
+            float e[8];
 #pragma unroll
-            for (int db = 0; db < D / 32; ++db) {
-                const bf16x8 af = *reinterpret_cast<const bf16x8*>(vr + db * 32 * Tile<D>::VP);
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, pf[g16], o[db], 0, 0, 0);
+            for (int j = 0; j < 8; ++j) {
+                e[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[g16 * 8 + j], sc, -mr));
+                l_part += e[j];
             }
+            bf16x8 pf;
+#pragma unroll
+            for (int j = 0; j < 8; j += 2) {
+                f32x2 two = {e[j], e[j + 1]};
+                bf16x2 b2 = __builtin_convertvector(two, bf16x2);
+                pf[j] = b2[0];
+                pf[j + 1] = b2[1];
+            }
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[g16][db], pf, o[db], 0, 0, 0);
         }
-        buf ^= 1;
+        step_barrier<2 * DMA_PER_STEP>();   // the loads of this step and the one before may be in flight
+    };
+
+    if (t_begin < t_end) {
+        f32x16 s_a, s_b;
+        dma_k(t_begin, ks0);
+        dma_k(t_begin + 1, ks1);
+        dma_k(t_begin + 2, ks2);
+        dma_k(t_begin + 3, ks3);
+        dma_v(t_begin, vs0);
+        dma_v(t_begin + 1, vs1);
+        dma_v(t_begin + 2, vs2);
+        step_barrier<0>();
+        {
+            bf16x8 kf0[D / 16];
+            load_k(ks0, kf0);
+            qk(kf0, s_a);
+        }
+        step_barrier<0>();         // K(t_begin) is consumed: its stage is refilled in the first step
+        // step i (mod 4) of this workgroup: S(t) in s_a / s_b alternately, K(t+1) in stage i+1,
+        // V(t) in stage i; K(t+4) goes to stage i, V(t+3) to stage i+3
+        int t = t_begin;
+        while (true) {
+            step(t, s_a, s_b, ks1, ks0, vs0, vs3);
+            if (++t == t_end) break;
+            step(t, s_b, s_a, ks2, ks1, vs1, vs0);
+            if (++t == t_end) break;
+            step(t, s_a, s_b, ks3, ks2, vs2, vs1);
+            if (++t == t_end) break;
+            step(t, s_b, s_a, ks0, ks3, vs3, vs2);
+            if (++t == t_end) break;
+        }
+        wait_vmem();               // no load may still be writing LDS when the workgroup retires
     }
 
-    const float l_tot = l_part + __shfl_xor(l_part, 32);
+    const float l_tot = pair_sum(l_part);
     if (a.n_splits == 1) {
         if (row_ok) {
             const float inv = 1.f / l_tot;
@@ -367,17 +464,8 @@ hipError_t launch(const AttnProblem& p, const AttnPlan& plan, void* workspace, h
         a.part_o = static_cast<float*>(workspace);
         a.part_ml = a.part_o + ik * plan.n_splits * plan.m_tiles * BM * (int64_t)D;
     }
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)Tile<D>::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     const int64_t nb = ik * plan.n_splits * plan.m_tiles;
-    hipLaunchKernelGGL(attn_bf16_kernel<D>, dim3((unsigned)nb), dim3(THREADS), Tile<D>::LDS_BYTES,
-                       stream, a);
+    hipLaunchKernelGGL(attn_bf16_kernel<D>, dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (plan.n_splits > 1) {
@@ -404,7 +492,7 @@ AttnPlan attn_bf16_plan(const AttnProblem& p) {
     const int64_t target = 512;              // about two workgroups per CU
     if (base < target) {
         splits = (int)((target + base - 1) / base);
-        const int cap = n_tiles / 4 > 1 ? n_tiles / 4 : 1;   // at least 4 tiles per split
+        const int cap = n_tiles / 8 > 1 ? n_tiles / 8 : 1;   // at least 8 tiles (256 keys) per split
         if (splits > cap) splits = cap;
     }
     plan.n_splits = splits;
