@@ -23,9 +23,9 @@
 // Pipeline.  Tiles are 32 keys; per tile t one barrier.  While the softmax of tile t runs on
 // the vector ALU, the matrix cores compute S^T of tile t+1 and the PV product of tile t;
 // K(t+4) and V(t+3) are being fetched, so a load has three steps to land.  The four K and
-// four V stages are eight distinct arrays and the loop is unrolled by four, so every LDS
-// access names its array (the compiler then orders reads only against loads into the same
-// array).  Every step issues the same number of loads per wave (past the end of the tile
+// four V stages sit in one LDS array and the loop is unrolled by four, so every stage is an
+// immediate offset of its ds_read.  Steps whose tiles are whole tiles of segment A run a
+// variant without masking and with constant load offsets.  Every step issues the same number of loads per wave (past the end of the tile
 // list the last tile is fetched again into a stage nobody reads), so "all but the newest
 // N loads have landed" is one s_waitcnt vmcnt(N).
 #include <type_traits>
@@ -116,20 +116,20 @@ __device__ inline float pair_sum(float v) {
 template <int N>
 __device__ inline void step_barrier() {
     static_assert(N >= 0 && N < 16, "vmcnt immediate");
+    __builtin_amdgcn_sched_barrier(0);     // nothing of this step sinks below its barrier
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+    __builtin_amdgcn_sched_barrier(0);
 }
+
+template <int I>
+using IC = std::integral_constant<int, I>;
 
 template <int D>
 __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     typedef Cfg<D> C;
-    __shared__ __attribute__((aligned(1024))) bf16_t ks0[C::TILE_ELEMS];
-    __shared__ __attribute__((aligned(1024))) bf16_t ks1[C::TILE_ELEMS];
-    __shared__ __attribute__((aligned(1024))) bf16_t ks2[C::TILE_ELEMS];
-    __shared__ __attribute__((aligned(1024))) bf16_t ks3[C::TILE_ELEMS];
-    __shared__ __attribute__((aligned(1024))) bf16_t vs0[C::TILE_ELEMS];
-    __shared__ __attribute__((aligned(1024))) bf16_t vs1[C::TILE_ELEMS];
-    __shared__ __attribute__((aligned(1024))) bf16_t vs2[C::TILE_ELEMS];
-    __shared__ __attribute__((aligned(1024))) bf16_t vs3[C::TILE_ELEMS];
+    // K stages 0..3, then V stages 0..3; one array so that every stage is a constant offset
+    __shared__ __attribute__((aligned(1024))) bf16_t lds[2 * STAGES * C::TILE_ELEMS];
+    constexpr uint32_t TILE_B = C::TILE_ELEMS * 2;           // bytes per stage
 
     const AttnProblem& p = a.p;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -146,10 +146,11 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
 
     const ItemSegs seg = item_segments(p, item);
     const int64_t row_stride = (int64_t)p.n_kv_heads * D;
-    const bf16_t* ka = static_cast<const bf16_t*>(p.k_a) + seg.a_off * row_stride + kvh * D;
-    const bf16_t* va = static_cast<const bf16_t*>(p.v_a) + seg.a_off * row_stride + kvh * D;
-    const bf16_t* kb = static_cast<const bf16_t*>(p.k_b) + seg.b_off * row_stride + kvh * D;
-    const bf16_t* vb = static_cast<const bf16_t*>(p.v_b) + seg.b_off * row_stride + kvh * D;
+    const uint32_t row_stride_b = (uint32_t)row_stride * 2u;
+    const char* ka = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_a) + seg.a_off * row_stride + kvh * D);
+    const char* va = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.v_a) + seg.a_off * row_stride + kvh * D);
+    const char* kb = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_b) + seg.b_off * row_stride + kvh * D);
+    const char* vb = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.v_b) + seg.b_off * row_stride + kvh * D);
 
     const int m_rows = p.len_b * G;
     const int m0 = mt * BM;
@@ -157,8 +158,10 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     const int tok = row / G;                      // its token inside the item
     const bool row_ok = row < m_rows;
 
-    // tile list: tiles_a unmasked tiles, then the causal tiles this row block can see
+    // tile list: tiles_a tiles of segment A (the first a_full of them whole and unmasked), then
+    // the causal tiles of segment B this row block can see
     const int tiles_a = (seg.len_a + BN - 1) / BN;
+    const int a_full = seg.len_a / BN;
     const int tiles_b_all = (p.len_b + BN - 1) / BN;
     int last_tok = (m0 + BM - 1) / G;
     if (last_tok > p.len_b - 1) last_tok = p.len_b - 1;
@@ -169,21 +172,27 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     if (t_end > n_tiles) t_end = n_tiles;
 
     // ---- lane-constant addressing -----------------------------------------------------
+    const uint32_t lds0 = lds_addr_of(lds);
     // global -> LDS: load j of this wave fills LDS rows dma_row + j*RPI, chunk slot dma_p
     const int dma_row = wave * C::DMA_PER_WAVE * C::RPI + lane / C::CH;
     const int dma_p = lane % C::CH;
-    int dma_coff[C::DMA_PER_WAVE];               // element offset of the chunk to fetch
+    uint32_t dma_coff[C::DMA_PER_WAVE];          // byte offset of the chunk to fetch inside its row
+    uint32_t dma_off[C::DMA_PER_WAVE];           // byte offset of that chunk inside a whole tile
 #pragma unroll
-    for (int j = 0; j < C::DMA_PER_WAVE; ++j)
-        dma_coff[j] = (dma_p ^ swz<D>(dma_row + j * C::RPI)) * 8;
-    // K operand (A of S^T = K Q^T): key row col, dims ks*16 + hh*8 .. +8
-    int k_off[D / 16];
+    for (int j = 0; j < C::DMA_PER_WAVE; ++j) {
+        dma_coff[j] = (uint32_t)(dma_p ^ swz<D>(dma_row + j * C::RPI)) * 16u;
+        dma_off[j] = (uint32_t)(dma_row + j * C::RPI) * row_stride_b + dma_coff[j];
+    }
+    const uint32_t dma_lds = lds0 + (uint32_t)(wave * C::DMA_PER_WAVE) * 1024u;   // + stage, + j KB
+    // K operand (A of S^T = K Q^T): key row col, dims ks*16 + hh*8 .. +8; LDS byte addresses
+    uint32_t k_addr[D / 16];
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) k_off[ks] = col * D + (((ks * 2 + hh) ^ swz<D>(col)) * 8);
+    for (int ks = 0; ks < D / 16; ++ks)
+        k_addr[ks] = lds0 + (uint32_t)(col * D + (((ks * 2 + hh) ^ swz<D>(col)) * 8)) * 2u;
     // V^T operand (A of O^T = V^T P^T) through the transposing read: this lane supplies the
     // address of 4 dims of one key; which key and dims follows from the lane's place in its
     // group of 16.  r picks the first or second set of 4 k-slots of the MFMA.
-    int v_off[2][D / 32];
+    uint32_t v_addr[2][D / 32];
     {
         const int gq = lane >> 4, i16 = lane & 15, qd = i16 & 3, jk = i16 >> 2;
         const int cl = (gq & 1) * 2 + (qd >> 1), half = qd & 1;
@@ -192,39 +201,34 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
             const int keyl = r * 8 + hh * 4 + jk;
 #pragma unroll
             for (int db = 0; db < D / 32; ++db)
-                v_off[r][db] = keyl * D + (((db * 4 + cl) ^ swz<D>(keyl)) * 8) + half * 4;
+                v_addr[r][db] = lds0 + STAGES * TILE_B +
+                    (uint32_t)(keyl * D + (((db * 4 + cl) ^ swz<D>(keyl)) * 8) + half * 4) * 2u;
         }
     }
 
-    // Fetches tile t (clamped to the last tile of this workgroup's list) of K and V.  In a full
-    // tile the per-lane byte offsets are constants; only a segment's ragged last tile
-    // recomputes them, re-reading the segment's last key for the rows past its end.
-    const uint32_t row_stride_b = (uint32_t)row_stride * 2u;
-    uint32_t dma_off[C::DMA_PER_WAVE];
+    // A whole tile inside segment A: constant per-lane offsets, only the base moves.
+    auto dma_fast = [&](const char* base, uint32_t stage_b) {
 #pragma unroll
-    for (int j = 0; j < C::DMA_PER_WAVE; ++j)
-        dma_off[j] = (uint32_t)(dma_row + j * C::RPI) * row_stride_b + (uint32_t)dma_coff[j] * 2u;
-    auto dma_tile = [&](int t, const bf16_t* seg_a, const bf16_t* seg_b, bf16_t* dst) {
+        for (int j = 0; j < C::DMA_PER_WAVE; ++j) dma16(base, dma_off[j], dma_lds + stage_b + j * 1024u);
+    };
+    const int64_t tile_stride_b = BN * (int64_t)row_stride_b;
+    const char* k_run = nullptr;                 // next K / V tile of the plain steps
+    const char* v_run = nullptr;
+    // Any tile (clamped to the last tile of this workgroup's list); a segment's ragged last
+    // tile re-reads the segment's last key for the rows past its end.
+    auto dma_any = [&](const char* seg_a, const char* seg_b, int t, uint32_t stage_b) {
         t = t < t_end - 1 ? t : t_end - 1;
         const bool in_b = t >= tiles_a;
         const int key0 = (in_b ? t - tiles_a : t) * BN;
         const int n_valid = (in_b ? p.len_b : seg.len_a) - key0;
-        const char* base = reinterpret_cast<const char*>(in_b ? seg_b : seg_a) + (int64_t)key0 * row_stride_b;
-        const uint32_t l = lds_addr_of(dst) + (uint32_t)(wave * C::DMA_PER_WAVE) * 1024u;
-        if (n_valid >= BN) {
+        const char* base = (in_b ? seg_b : seg_a) + (int64_t)key0 * row_stride_b;
 #pragma unroll
-            for (int j = 0; j < C::DMA_PER_WAVE; ++j) dma16(base, dma_off[j], l + j * 1024u);
-        } else {
-#pragma unroll
-            for (int j = 0; j < C::DMA_PER_WAVE; ++j) {
-                int r = dma_row + j * C::RPI;
-                r = r < n_valid - 1 ? r : n_valid - 1;
-                dma16(base, (uint32_t)r * row_stride_b + (uint32_t)dma_coff[j] * 2u, l + j * 1024u);
-            }
+        for (int j = 0; j < C::DMA_PER_WAVE; ++j) {
+            int r = dma_row + j * C::RPI;
+            r = r < n_valid - 1 ? r : n_valid - 1;
+            dma16(base, (uint32_t)r * row_stride_b + dma_coff[j], dma_lds + stage_b + j * 1024u);
         }
     };
-    auto dma_k = [&](int t, bf16_t* dst) { dma_tile(t, ka, kb, dst); };
-    auto dma_v = [&](int t, bf16_t* dst) { dma_tile(t, va, vb, dst); };
     constexpr int DMA_PER_STEP = 2 * C::DMA_PER_WAVE;
 
     // Q fragments (B operand of S^T = K Q^T): lane holds row `row`, dims ks*16 + hh*8 .. +8
@@ -258,45 +262,58 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
         for (int ks = 0; ks < D / 16; ++ks)
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], s, 0, 0, 0);
     };
-    auto load_k = [&](const bf16_t* kt, bf16x8 (&kf)[D / 16]) {
+    auto load_k = [&](uint32_t stage_b, bf16x8 (&kf)[D / 16]) {
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) kf[ks] = *reinterpret_cast<const bf16x8*>(kt + k_off[ks]);
+        for (int ks = 0; ks < D / 16; ++ks)
+            kf[ks] = *reinterpret_cast<LDS_AS const bf16x8*>(k_addr[ks] + stage_b);
     };
 
-    // One pipeline step for tile t.  s_cur holds S^T(t); S^T(t+1) goes to s_next.  k_next holds
-    // K(t+1), v_cur holds V(t); K(t+4) and V(t+3) are fetched into k_load / v_load, the stages
-    // whose tiles (K(t), V(t-1)) were consumed in the step before.
-    auto step = [&](int t, f32x16& s_cur, f32x16& s_next, const bf16_t* k_next, bf16_t* k_load,
-                    const bf16_t* v_cur, bf16_t* v_load) {
-        dma_k(t + 4, k_load);
-        dma_v(t + 3, v_load);
+    // One pipeline step for tile t.  s_cur holds S^T(t); S^T(t+1) goes to s_next.  Stage KN
+    // holds K(t+1), stage VC holds V(t); K(t+4) and V(t+3) are fetched into stages KL / VL,
+    // whose tiles (K(t), V(t-1)) were consumed in the step before.  PLAIN steps are those
+    // whose tile and whose fetched tiles are whole tiles of segment A: no mask, no clamping.
+    auto step = [&](int t, f32x16& s_cur, f32x16& s_next, auto kn, auto kl, auto vc, auto vl, auto plain) {
+        constexpr uint32_t KN = decltype(kn)::value * TILE_B, KL = decltype(kl)::value * TILE_B;
+        constexpr uint32_t VC = decltype(vc)::value * TILE_B, VL = decltype(vl)::value * TILE_B;
+        constexpr bool PLAIN = decltype(plain)::value;
+        if (PLAIN) {
+            dma_fast(k_run, KL);
+            dma_fast(v_run, STAGES * TILE_B + VL);
+            k_run += tile_stride_b;
+            v_run += tile_stride_b;
+        } else {
+            dma_any(ka, kb, t + 4, KL);
+            dma_any(va, vb, t + 3, STAGES * TILE_B + VL);
+        }
         // All LDS operand reads of this step are issued first; the running-maximum work below
         // covers their latency, and the MFMAs then issue back to back.
         bf16x8 kf[D / 16];
-        load_k(k_next, kf);
+        load_k(KN, kf);
         bf16x8 vf[2][D / 32];
         auto load_v = [&](int g16) {
 #pragma unroll
             for (int db = 0; db < D / 32; ++db) {
                 const tr4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                    (LDS_AS tr4_t*)(LDS_AS void*)(v_cur + g16 * 16 * D + v_off[0][db]));
+                    reinterpret_cast<LDS_AS tr4_t*>(v_addr[0][db] + VC + g16 * 16 * D * 2));
                 const tr4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                    (LDS_AS tr4_t*)(LDS_AS void*)(v_cur + g16 * 16 * D + v_off[1][db]));
+                    reinterpret_cast<LDS_AS tr4_t*>(v_addr[1][db] + VC + g16 * 16 * D * 2));
                 vf[g16][db] = __builtin_shufflevector(__builtin_bit_cast(bf16x4, lo),
                                                       __builtin_bit_cast(bf16x4, hi), 0, 1, 2, 3, 4, 5, 6, 7);
             }
         };
         load_v(0);
         __builtin_amdgcn_sched_barrier(0);
-        // ---- visibility: keys [0, lim) of this tile are visible to this lane's row
-        const bool in_b = t >= tiles_a;
-        const int key0 = (in_b ? t - tiles_a : t) * BN;
-        if (in_b || key0 + BN > seg.len_a) {
-            const int lim = (in_b ? (tok + 1 < p.len_b ? tok + 1 : p.len_b) : seg.len_a) - key0;
+        if (!PLAIN) {
+            // ---- visibility: keys [0, lim) of this tile are visible to this lane's row
+            const bool in_b = t >= tiles_a;
+            const int key0 = (in_b ? t - tiles_a : t) * BN;
+            if (in_b || key0 + BN > seg.len_a) {
+                const int lim = (in_b ? (tok + 1 < p.len_b ? tok + 1 : p.len_b) : seg.len_a) - key0;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int key = (j >> 2) * 8 + hh * 4 + (j & 3);
-                s_cur[j] = key < lim ? s_cur[j] : -INFINITY;
+                for (int j = 0; j < 16; ++j) {
+                    const int key = (j >> 2) * 8 + hh * 4 + (j & 3);
+                    s_cur[j] = key < lim ? s_cur[j] : -INFINITY;
+                }
             }
         }
         // ---- running maximum, one query per lane pair (lane, lane ^ 32)
@@ -318,6 +335,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
         const float mr = (m_ref == -INFINITY) ? 0.f : m_ref;
 
         // ---- matrix cores: S^T(t+1); vector ALU: exp of tile t; then O^T += V^T P^T
+        __builtin_amdgcn_s_setprio(3);     // the MFMA-carrying part of the step goes first on this SIMD
         qk(kf, s_next);            // past the last tile this works on a stale stage and is unused
         load_v(1);
 #pragma unroll
@@ -340,37 +358,52 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
             for (int db = 0; db < D / 32; ++db)
                 o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[g16][db], pf, o[db], 0, 0, 0);
         }
+        __builtin_amdgcn_s_setprio(0);
         step_barrier<2 * DMA_PER_STEP>();   // the loads of this step and the one before may be in flight
     };
 
     if (t_begin < t_end) {
         f32x16 s_a, s_b;
-        dma_k(t_begin, ks0);
-        dma_k(t_begin + 1, ks1);
-        dma_k(t_begin + 2, ks2);
-        dma_k(t_begin + 3, ks3);
-        dma_v(t_begin, vs0);
-        dma_v(t_begin + 1, vs1);
-        dma_v(t_begin + 2, vs2);
+        constexpr uint32_t VB = STAGES * TILE_B;
+        dma_any(ka, kb, t_begin, 0);
+        dma_any(ka, kb, t_begin + 1, TILE_B);
+        dma_any(ka, kb, t_begin + 2, 2 * TILE_B);
+        dma_any(ka, kb, t_begin + 3, 3 * TILE_B);
+        dma_any(va, vb, t_begin, VB);
+        dma_any(va, vb, t_begin + 1, VB + TILE_B);
+        dma_any(va, vb, t_begin + 2, VB + 2 * TILE_B);
         step_barrier<0>();
         {
             bf16x8 kf0[D / 16];
-            load_k(ks0, kf0);
+            load_k(0, kf0);
             qk(kf0, s_a);
         }
         step_barrier<0>();         // K(t_begin) is consumed: its stage is refilled in the first step
-        // step i (mod 4) of this workgroup: S(t) in s_a / s_b alternately, K(t+1) in stage i+1,
-        // V(t) in stage i; K(t+4) goes to stage i, V(t+3) to stage i+3
+        // Step i (mod 4) of this workgroup: S(t) in s_a / s_b alternately, K(t+1) in stage i+1,
+        // V(t) in stage i; K(t+4) goes to stage i, V(t+3) to stage i+3.  Groups of four steps
+        // run the plain variant while all their tiles, and the tiles they fetch, are whole
+        // unmasked tiles of segment A; the rest runs the general variant.
         int t = t_begin;
-        while (true) {
-            step(t, s_a, s_b, ks1, ks0, vs0, vs3);
+        const int t_plain = (a_full < t_end ? a_full : t_end) - 8;   // t + 3 + 4 < a_full for the group
+        const std::false_type general;
+        const std::true_type plain;
+        k_run = ka + (t + 4) * tile_stride_b;
+        v_run = va + (t + 3) * tile_stride_b;
+        for (; t <= t_plain; t += 4) {
+            step(t, s_a, s_b, IC<1>{}, IC<0>{}, IC<0>{}, IC<3>{}, plain);
+            step(t + 1, s_b, s_a, IC<2>{}, IC<1>{}, IC<1>{}, IC<0>{}, plain);
+            step(t + 2, s_a, s_b, IC<3>{}, IC<2>{}, IC<2>{}, IC<1>{}, plain);
+            step(t + 3, s_b, s_a, IC<0>{}, IC<3>{}, IC<3>{}, IC<2>{}, plain);
+        }
+        while (t < t_end) {
+            step(t, s_a, s_b, IC<1>{}, IC<0>{}, IC<0>{}, IC<3>{}, general);
             if (++t == t_end) break;
-            step(t, s_b, s_a, ks2, ks1, vs1, vs0);
+            step(t, s_b, s_a, IC<2>{}, IC<1>{}, IC<1>{}, IC<0>{}, general);
             if (++t == t_end) break;
-            step(t, s_a, s_b, ks3, ks2, vs2, vs1);
+            step(t, s_a, s_b, IC<3>{}, IC<2>{}, IC<2>{}, IC<1>{}, general);
             if (++t == t_end) break;
-            step(t, s_b, s_a, ks0, ks3, vs3, vs2);
-            if (++t == t_end) break;
+            step(t, s_b, s_a, IC<0>{}, IC<3>{}, IC<3>{}, IC<2>{}, general);
+            ++t;
         }
         wait_vmem();               // no load may still be writing LDS when the workgroup retires
     }
