@@ -209,7 +209,7 @@ rekv_status rekv_retrieve_topk(rekv_ctx* c, const float* frame_keys, int64_t fra
     if ((size_t)(d_prime + 1) * sizeof(float) > 48 * 1024)
         return fail(c, REKV_ERR_UNSUPPORTED, "rekv_retrieve_topk: Hkv*D=%d exceeds 12287", d_prime);
     if (n_questions > 65535) return fail(c, REKV_ERR_UNSUPPORTED, "rekv_retrieve_topk: at most 65535 questions per call");
-    const size_t qv_bytes = ((size_t)n_questions * d_prime * sizeof(float) + 255) & ~size_t(255);
+    const size_t qv_bytes = ((size_t)n_questions * c->shape.n_q_heads * c->shape.head_dim * sizeof(float) + 255) & ~size_t(255);
     const size_t sc_bytes = scores ? 0 : (size_t)n_questions * n_frames * sizeof(float);
     rekv_status s = reserve(c, qv_bytes + sc_bytes);
     if (s != REKV_OK) return s;

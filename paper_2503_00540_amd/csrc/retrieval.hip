@@ -67,62 +67,45 @@ __global__ __launch_bounds__(256) void frame_keys_kernel(const void* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------
-// Question vector: mean over the N_q tokens and over the G query heads of each KV group.
-// grid = (questions, D' / 256 rounded up); a thread owns one of the D' output entries.
-// ---------------------------------------------------------------------------------------
-template <bool BF16>
-__global__ __launch_bounds__(256) void pool_question_kernel(const void* __restrict__ q, int n_q,
-                                                            int hq, int hkv, int d,
-                                                            float* __restrict__ q_vec) {
-    const int d_prime = hkv * d, g_sz = hq / hkv;
-    const int c = blockIdx.y * 256 + threadIdx.x;
-    if (c >= d_prime) return;
-    const int g = c / d, dd = c % d;
-    const int64_t qi = blockIdx.x;
-    float acc = 0.f;
-    for (int t = 0; t < n_q; ++t)
-        for (int i = 0; i < g_sz; ++i) {
-            const int64_t e = ((qi * n_q + t) * hq + g * g_sz + i) * d + dd;
-            if (BF16) acc += __uint_as_float((uint32_t)static_cast<const uint16_t*>(q)[e] << 16);
-            else acc += static_cast<const float*>(q)[e];
-        }
-    q_vec[qi * d_prime + c] = acc / (float)(n_q * g_sz);
-}
-
-// ---------------------------------------------------------------------------------------
-// Eq. 2: one wavefront per frame computes <v,q>, |v|^2 for QB questions at a time; the
-// question vectors (and |q|^2) sit in LDS.  grid = (frame blocks, question blocks).
+// Question vector and Eq. 2.  The token mean of a question's queries, per query head, comes
+// from the same column-mean kernel as the frame vectors (the question is a "frame" of N_q
+// rows of Hq*D columns).  The score kernel finishes the pooling - the mean over the G query
+// heads of each KV group - while it stages the question vectors in LDS, then one wavefront
+// per frame computes <v,q> and |v|^2 for up to QB questions at a time.
+// grid = (frame blocks, question blocks); wavefronts stride over the frames.
 // ---------------------------------------------------------------------------------------
 constexpr int QB = 8;            // questions sharing one pass over a frame-key table
 constexpr int SCORE_WAVES = 4;
-constexpr int FRAMES_PER_WAVE = 4;
 
 __global__ __launch_bounds__(SCORE_WAVES * 64) void score_kernel(
-    const float* __restrict__ frame_keys, int64_t fk_stride, int n_frames, int d_prime,
-    const float* __restrict__ q_vec, int n_questions, int qb, float* __restrict__ scores) {
+    const float* __restrict__ frame_keys, int64_t fk_stride, int n_frames, int hq, int hkv, int d,
+    const float* __restrict__ q_heads, int n_questions, int qb, float* __restrict__ scores) {
     extern __shared__ float qs[];            // [qb][d_prime] then [qb] squared norms
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int d_prime = hkv * d, g_sz = hq / hkv;
     // qb questions share one pass over the table (1 when every question has its own table)
     const int q0 = blockIdx.y * qb;
     const int nq_here = n_questions - q0 < qb ? n_questions - q0 : qb;
     float* qn = qs + qb * d_prime;
-    for (int i = threadIdx.x; i < nq_here * d_prime; i += blockDim.x)
-        qs[i] = q_vec[(int64_t)q0 * d_prime + i];
+    const float inv_g = 1.f / (float)g_sz;
+    for (int i = threadIdx.x; i < nq_here * d_prime; i += blockDim.x) {
+        const int w = i / d_prime, c = i - w * d_prime;
+        const int g = c / d, dd = c - g * d;
+        const float* src = q_heads + ((int64_t)(q0 + w) * hq + g * g_sz) * d + dd;
+        float acc = 0.f;
+        for (int j = 0; j < g_sz; ++j) acc += src[j * d];
+        qs[i] = acc * inv_g;
+    }
     __syncthreads();
-    if (wave < nq_here) {                    // wave w reduces |q_w|^2 (qb <= 8 needs two rounds)
-        for (int w = wave; w < nq_here; w += SCORE_WAVES) {
-            float s = 0.f;
-            for (int i = lane; i < d_prime; i += 64) s += qs[w * d_prime + i] * qs[w * d_prime + i];
-            s = wave_sum(s);
-            if (lane == 0) qn[w] = s;
-        }
+    for (int w = wave; w < nq_here; w += SCORE_WAVES) {
+        float s = 0.f;
+        for (int i = lane; i < d_prime; i += 64) s += qs[w * d_prime + i] * qs[w * d_prime + i];
+        s = wave_sum(s);
+        if (lane == 0) qn[w] = s;
     }
     __syncthreads();
     const float* table = frame_keys + (int64_t)q0 * fk_stride;
-    const int f0 = (blockIdx.x * SCORE_WAVES + wave) * FRAMES_PER_WAVE;
-    for (int ff = 0; ff < FRAMES_PER_WAVE; ++ff) {
-        const int f = f0 + ff;
-        if (f >= n_frames) break;
+    for (int f = blockIdx.x * SCORE_WAVES + wave; f < n_frames; f += gridDim.x * SCORE_WAVES) {
         const float* v = table + (int64_t)f * d_prime;
         float dot[QB], vv = 0.f;
 #pragma unroll
@@ -273,24 +256,21 @@ hipError_t frame_keys_launch(const void* k, int n_frames, int tokens_per_frame, 
 
 hipError_t retrieve_launch(const RetrieveArgs& a, hipStream_t stream) {
     const int d_prime = a.n_kv_heads * a.head_dim;
-    dim3 pg((unsigned)a.n_questions, (unsigned)((d_prime + 255) / 256));
-    if (a.dtype == REKV_BF16)
-        hipLaunchKernelGGL(pool_question_kernel<true>, pg, dim3(256), 0, stream, a.q_question,
-                           a.n_q_tokens, a.n_q_heads, a.n_kv_heads, a.head_dim, a.q_vec);
-    else
-        hipLaunchKernelGGL(pool_question_kernel<false>, pg, dim3(256), 0, stream, a.q_question,
-                           a.n_q_tokens, a.n_q_heads, a.n_kv_heads, a.head_dim, a.q_vec);
-    hipError_t e = hipGetLastError();
+    // token mean per query head: [n_questions, Hq * D] fp32 in a.q_vec
+    hipError_t e = frame_keys_launch(a.q_question, a.n_questions, a.n_q_tokens, a.n_q_heads * a.head_dim,
+                                     a.dtype, a.q_vec, stream);
     if (e != hipSuccess) return e;
 
     // questions per block: up to QB on a shared table, as many as fit 48 KB of LDS
     int qb = a.frame_keys_stride ? 1 : QB;
     while (qb > 1 && (size_t)qb * (d_prime + 1) * sizeof(float) > 48 * 1024) qb >>= 1;
-    const int fpb = SCORE_WAVES * FRAMES_PER_WAVE;
-    dim3 sg((unsigned)((a.n_frames + fpb - 1) / fpb), (unsigned)((a.n_questions + qb - 1) / qb));
+    int fblocks = (a.n_frames + SCORE_WAVES - 1) / SCORE_WAVES;
+    if (fblocks > 4096) fblocks = 4096;
+    dim3 sg((unsigned)fblocks, (unsigned)((a.n_questions + qb - 1) / qb));
     const size_t lds = (size_t)qb * (d_prime + 1) * sizeof(float);
     hipLaunchKernelGGL(score_kernel, sg, dim3(SCORE_WAVES * 64), lds, stream, a.frame_keys,
-                       a.frame_keys_stride, a.n_frames, d_prime, a.q_vec, a.n_questions, qb, a.scores);
+                       a.frame_keys_stride, a.n_frames, a.n_q_heads, a.n_kv_heads, a.head_dim, a.q_vec,
+                       a.n_questions, qb, a.scores);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
 
