@@ -141,8 +141,10 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     int L = xcd_remap(blockIdx.x, nb);
     const int mt = L % a.m_tiles; L /= a.m_tiles;
     const int split = L % a.n_splits; L /= a.n_splits;
-    const int kvh = L % p.n_kv_heads;
-    const int item = L / p.n_kv_heads;
+    // KV head slowest: an XCD then works through consecutive chunks of one KV head, whose
+    // windows overlap, so its L2 keeps serving the same K/V rows
+    const int item = L % p.n_items;
+    const int kvh = L / p.n_items;
 
     const ItemSegs seg = item_segments(p, item);
     const int64_t row_stride = (int64_t)p.n_kv_heads * D;
