@@ -129,14 +129,18 @@ rekv_status rekv_retrieve_topk(rekv_ctx* ctx, const float* frame_keys, int64_t f
  * dense buffer per question, in the order idx gives them (ascending frame index).
  *
  *   src_k, src_v  [n_src_frames * N_f, Hkv, D] in HBM (src_on_host = 0) or in pinned host
- *                 memory (src_on_host = 1, host pointers; memory from hipHostMalloc)
+ *                 memory (src_on_host = 1 or 2, host pointers; memory from hipHostMalloc)
  *   idx           [n_questions, k] int32 on the device; entries < 0 are skipped and their
  *                 destination block is zero-filled; entries >= n_src_frames are an error
  *                 only on the host path (the device path skips them likewise)
  *   dst_k, dst_v  [n_questions, k * N_f, Hkv, D] in HBM
- * Host path: idx is copied to the host (the call blocks until `stream` reaches it), then
- * one async copy per frame and tensor runs on the context's side stream; `stream` waits
- * on an event for their completion, so later work on `stream` sees the data.
+ * Host path 1 (copy engine): idx is copied to the host (the call blocks until `stream`
+ * reaches it), then one async copy per run of consecutive frames and tensor goes to the
+ * context's side stream; `stream` waits on an event for their completion, so later work on
+ * `stream` sees the data.
+ * Host path 2 (zero-copy): the gather kernel itself reads the pinned arrays over the host
+ * link, on the side stream, ordered after `stream` and joined back into it; the host does not
+ * block and idx never leaves the device.  Out-of-range entries are skipped as on the device path.
  */
 rekv_status rekv_gather_kv(rekv_ctx* ctx, const void* src_k, const void* src_v,
                            int32_t src_on_host, int32_t n_src_frames, const int32_t* idx,

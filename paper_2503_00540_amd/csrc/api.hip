@@ -209,7 +209,8 @@ rekv_status rekv_retrieve_topk(rekv_ctx* c, const float* frame_keys, int64_t fra
     if ((size_t)(d_prime + 1) * sizeof(float) > 48 * 1024)
         return fail(c, REKV_ERR_UNSUPPORTED, "rekv_retrieve_topk: Hkv*D=%d exceeds 12287", d_prime);
     if (n_questions > 65535) return fail(c, REKV_ERR_UNSUPPORTED, "rekv_retrieve_topk: at most 65535 questions per call");
-    const size_t qv_bytes = ((size_t)n_questions * c->shape.n_q_heads * c->shape.head_dim * sizeof(float) + 255) & ~size_t(255);
+    const size_t qh_bytes = ((size_t)n_questions * c->shape.n_q_heads * c->shape.head_dim * sizeof(float) + 255) & ~size_t(255);
+    const size_t qv_bytes = qh_bytes + (((size_t)n_questions * d_prime * sizeof(float) + 255) & ~size_t(255));
     const size_t sc_bytes = scores ? 0 : (size_t)n_questions * n_frames * sizeof(float);
     rekv_status s = reserve(c, qv_bytes + sc_bytes);
     if (s != REKV_OK) return s;
@@ -219,7 +220,8 @@ rekv_status rekv_retrieve_topk(rekv_ctx* c, const float* frame_keys, int64_t fra
     a.n_q_heads = c->shape.n_q_heads; a.n_kv_heads = c->shape.n_kv_heads; a.head_dim = c->shape.head_dim;
     a.dtype = c->shape.dtype;
     a.idx = idx; a.n_sel = n_sel;
-    a.q_vec = static_cast<float*>(c->ws);
+    a.q_heads = static_cast<float*>(c->ws);
+    a.q_vec = reinterpret_cast<float*>(static_cast<char*>(c->ws) + qh_bytes);
     a.scores = scores ? scores : reinterpret_cast<float*>(static_cast<char*>(c->ws) + qv_bytes);
     hipError_t e = rekv::retrieve_launch(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? REKV_OK : fail_hip(c, "retrieval launch", e);
@@ -232,7 +234,7 @@ rekv_status rekv_gather_kv(rekv_ctx* c, const void* src_k, const void* src_v, in
     if (!src_k || !src_v || !idx || !dst_k || !dst_v) return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv: null pointer");
     if (!aligned16(src_k) || !aligned16(src_v) || !aligned16(dst_k) || !aligned16(dst_v))
         return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv: pointers must be 16-byte aligned");
-    if (n_src_frames <= 0 || n_questions <= 0 || k <= 0 || (src_on_host != 0 && src_on_host != 1))
+    if (n_src_frames <= 0 || n_questions <= 0 || k <= 0 || src_on_host < 0 || src_on_host > 2)
         return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv: n_src_frames=%d n_questions=%d k=%d src_on_host=%d",
                     n_src_frames, n_questions, k, src_on_host);
     const int64_t n_blocks = (int64_t)n_questions * k;
@@ -245,6 +247,26 @@ rekv_status rekv_gather_kv(rekv_ctx* c, const void* src_k, const void* src_v, in
         hipError_t e = rekv::gather_launch(src_k, src_v, n_src_frames, idx, (int)n_blocks, frame_bytes,
                                            dst_k, dst_v, stream);
         return e == hipSuccess ? REKV_OK : fail_hip(c, "gather launch", e);
+    }
+
+    if (src_on_host == 2) {
+        // Zero-copy host path: the gather kernel reads the pinned host arrays over the host link.
+        // It runs on the side stream after everything queued on `stream` (the index list is
+        // produced there); `stream` then waits for it.  No host synchronisation.
+        void *dk = nullptr, *dv = nullptr;
+        hipError_t e = hipHostGetDevicePointer(&dk, const_cast<void*>(src_k), 0);
+        if (e == hipSuccess) e = hipHostGetDevicePointer(&dv, const_cast<void*>(src_v), 0);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv: src is not pinned host memory (%s)", hipGetErrorString(e));
+        }
+        e = hipEventRecord(c->ev_main, stream);
+        if (e == hipSuccess) e = hipStreamWaitEvent(c->side, c->ev_main, 0);
+        if (e == hipSuccess)
+            e = rekv::gather_launch(dk, dv, n_src_frames, idx, (int)n_blocks, frame_bytes, dst_k, dst_v, c->side);
+        if (e == hipSuccess) e = hipEventRecord(c->ev_side, c->side);
+        if (e == hipSuccess) e = hipStreamWaitEvent(stream, c->ev_side, 0);
+        return e == hipSuccess ? REKV_OK : fail_hip(c, "rekv_gather_kv: zero-copy gather", e);
     }
 
     // Host path: bring the index list to the host, then one async copy per frame and tensor

@@ -77,7 +77,8 @@ struct RetrieveArgs {
     int32_t* idx;
     int32_t* n_sel;
     float* scores;   // [n_questions, n_frames], never NULL here (workspace if the caller gave none)
-    float* q_vec;    // [n_questions, Hq * D] workspace: token means per query head
+    float* q_heads;  // [n_questions, Hq * D] workspace: token means per query head
+    float* q_vec;    // [n_questions, D'] workspace: pooled question vectors
 };
 hipError_t retrieve_launch(const RetrieveArgs& a, hipStream_t stream);
 

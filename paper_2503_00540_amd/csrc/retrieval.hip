@@ -69,35 +69,66 @@ __global__ __launch_bounds__(256) void frame_keys_kernel(const void* __restrict_
 // ---------------------------------------------------------------------------------------
 // Question vector and Eq. 2.  The token mean of a question's queries, per query head, comes
 // from the same column-mean kernel as the frame vectors (the question is a "frame" of N_q
-// rows of Hq*D columns).  The score kernel finishes the pooling - the mean over the G query
-// heads of each KV group - while it stages the question vectors in LDS, then one wavefront
-// per frame computes <v,q> and |v|^2 for up to QB questions at a time.
-// grid = (frame blocks, question blocks); wavefronts stride over the frames.
+// rows of Hq*D columns); a small kernel then averages the G query heads of each KV group.
+// The score kernel stages the question vectors in LDS.  A wavefront then takes FR frames x
+// QBT questions at a time: every lane accumulates the FR*QBT partial dot
+// products (and the FR partial |v|^2) over its slice of the D' columns, and a transposing
+// butterfly leaves each total in one lane with one shuffle per total instead of six.
+// grid = (frame-group blocks, question blocks); wavefronts stride over the frame groups.
 // ---------------------------------------------------------------------------------------
-constexpr int QB = 8;            // questions sharing one pass over a frame-key table
 constexpr int SCORE_WAVES = 4;
 
-__global__ __launch_bounds__(SCORE_WAVES * 64) void score_kernel(
-    const float* __restrict__ frame_keys, int64_t fk_stride, int n_frames, int hq, int hkv, int d,
-    const float* __restrict__ q_heads, int n_questions, int qb, float* __restrict__ scores) {
-    extern __shared__ float qs[];            // [qb][d_prime] then [qb] squared norms
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+// q_vec[q][g*D + dd] = mean over the G heads of group g of q_heads[q][(g*G + i)*D + dd]
+__global__ __launch_bounds__(256) void group_mean_kernel(const float* __restrict__ q_heads, int hq, int hkv,
+                                                         int d, float* __restrict__ q_vec) {
     const int d_prime = hkv * d, g_sz = hq / hkv;
-    // qb questions share one pass over the table (1 when every question has its own table)
-    const int q0 = blockIdx.y * qb;
-    const int nq_here = n_questions - q0 < qb ? n_questions - q0 : qb;
-    float* qn = qs + qb * d_prime;
-    const float inv_g = 1.f / (float)g_sz;
-    for (int i = threadIdx.x; i < nq_here * d_prime; i += blockDim.x) {
-        const int w = i / d_prime, c = i - w * d_prime;
-        const int g = c / d, dd = c - g * d;
-        const float* src = q_heads + ((int64_t)(q0 + w) * hq + g * g_sz) * d + dd;
-        float acc = 0.f;
-        for (int j = 0; j < g_sz; ++j) acc += src[j * d];
-        qs[i] = acc * inv_g;
+    const int c = blockIdx.y * 256 + threadIdx.x;
+    if (c >= d_prime) return;
+    const int g = c / d, dd = c - g * d;
+    const float* src = q_heads + ((int64_t)blockIdx.x * hq + g * g_sz) * d + dd;
+    float acc = 0.f;
+    for (int j = 0; j < g_sz; ++j) acc += src[j * d];
+    q_vec[(int64_t)blockIdx.x * d_prime + c] = acc / (float)g_sz;
+}
+
+// Sums v[i] over the 64 lanes for all i at once.  Returns, in every lane, the total of the
+// value whose index is the lane's top log2(N) bits (lane >> (6 - log2 N)).
+template <int N>
+__device__ inline float transpose_reduce(float (&v)[N], int lane) {
+    int n = N;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        if (n > 1) {
+            const int half = n / 2;
+            const bool up = (lane & off) != 0;
+#pragma unroll
+            for (int i = 0; i < half; ++i) {
+                const float keep = up ? v[i + half] : v[i];
+                const float send = up ? v[i] : v[i + half];
+                v[i] = keep + __shfl_xor(send, off);
+            }
+            n = half;
+        } else {
+            v[0] += __shfl_xor(v[0], off);
+        }
     }
+    return v[0];
+}
+
+template <int FR, int QBT>
+__global__ __launch_bounds__(SCORE_WAVES * 64) void score_kernel(
+    const float* __restrict__ frame_keys, int64_t fk_stride, int n_frames, int d_prime,
+    const float* __restrict__ q_vec, int n_questions, float* __restrict__ scores) {
+    static_assert(FR * QBT <= 64 && (FR & (FR - 1)) == 0 && (QBT & (QBT - 1)) == 0, "butterfly sizes");
+    extern __shared__ float qs[];            // [QBT][d_prime] then [QBT] squared norms
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int q0 = blockIdx.y * QBT;
+    const int nq_here = n_questions - q0 < QBT ? n_questions - q0 : QBT;
+    float* qn = qs + QBT * d_prime;
+    for (int i = threadIdx.x; i < QBT * d_prime; i += blockDim.x)     // absent questions stay zero
+        qs[i] = i < nq_here * d_prime ? q_vec[(int64_t)q0 * d_prime + i] : 0.f;
     __syncthreads();
-    for (int w = wave; w < nq_here; w += SCORE_WAVES) {
+    for (int w = wave; w < QBT; w += SCORE_WAVES) {
         float s = 0.f;
         for (int i = lane; i < d_prime; i += 64) s += qs[w * d_prime + i] * qs[w * d_prime + i];
         s = wave_sum(s);
@@ -105,31 +136,43 @@ __global__ __launch_bounds__(SCORE_WAVES * 64) void score_kernel(
     }
     __syncthreads();
     const float* table = frame_keys + (int64_t)q0 * fk_stride;
-    for (int f = blockIdx.x * SCORE_WAVES + wave; f < n_frames; f += gridDim.x * SCORE_WAVES) {
-        const float* v = table + (int64_t)f * d_prime;
-        float dot[QB], vv = 0.f;
+    constexpr int LOG_N = __builtin_ctz(FR * QBT), LOG_FR = __builtin_ctz(FR);
+    for (int f0 = (blockIdx.x * SCORE_WAVES + wave) * FR; f0 < n_frames; f0 += gridDim.x * SCORE_WAVES * FR) {
+        float acc[FR * QBT], vv[FR];
 #pragma unroll
-        for (int w = 0; w < QB; ++w) dot[w] = 0.f;
-        for (int i = lane * 4; i < d_prime; i += 256) {
-            const float4 x = *reinterpret_cast<const float4*>(v + i);
-            vv += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+        for (int i = 0; i < FR * QBT; ++i) acc[i] = 0.f;
 #pragma unroll
-            for (int w = 0; w < QB; ++w)
-                if (w < nq_here) {
-                    const float4 y = *reinterpret_cast<const float4*>(qs + w * d_prime + i);
-                    dot[w] += x.x * y.x + x.y * y.y + x.z * y.z + x.w * y.w;
-                }
+        for (int i = 0; i < FR; ++i) vv[i] = 0.f;
+        const float* vrow[FR];
+#pragma unroll
+        for (int fr = 0; fr < FR; ++fr) {
+            const int f = f0 + fr < n_frames ? f0 + fr : n_frames - 1;   // tail: re-read the last frame
+            vrow[fr] = table + (int64_t)f * d_prime;
         }
-        vv = wave_sum(vv);
+        for (int i = lane * 4; i < d_prime; i += 256) {
+            float4 x[FR];
 #pragma unroll
-        for (int w = 0; w < QB; ++w)
-            if (w < nq_here) {
-                const float dsum = wave_sum(dot[w]);
-                if (lane == 0) {
-                    const float den = sqrtf(vv) * sqrtf(qn[w]);
-                    scores[(int64_t)(q0 + w) * n_frames + f] = den > 0.f ? dsum / den : 0.f;
-                }
+            for (int fr = 0; fr < FR; ++fr) {
+                x[fr] = *reinterpret_cast<const float4*>(vrow[fr] + i);
+                vv[fr] += x[fr].x * x[fr].x + x[fr].y * x[fr].y + x[fr].z * x[fr].z + x[fr].w * x[fr].w;
             }
+#pragma unroll
+            for (int w = 0; w < QBT; ++w) {
+                const float4 y = *reinterpret_cast<const float4*>(qs + w * d_prime + i);
+#pragma unroll
+                for (int fr = 0; fr < FR; ++fr)
+                    acc[fr * QBT + w] += x[fr].x * y.x + x[fr].y * y.y + x[fr].z * y.z + x[fr].w * y.w;
+            }
+        }
+        const float dsum = transpose_reduce<FR * QBT>(acc, lane);
+        const float vsum = transpose_reduce<FR>(vv, lane);
+        const int idx = lane >> (6 - LOG_N);                 // = fr * QBT + w
+        const int fr = lane >> (6 - LOG_FR), w = idx & (QBT - 1);
+        const bool writer = (lane & ((1 << (6 - LOG_N)) - 1)) == 0;
+        if (writer && f0 + fr < n_frames && w < nq_here) {
+            const float den = sqrtf(vsum) * sqrtf(qn[w]);
+            scores[(int64_t)(q0 + w) * n_frames + f0 + fr] = den > 0.f ? dsum / den : 0.f;
+        }
     }
 }
 
@@ -148,24 +191,24 @@ __device__ inline uint32_t order_key(float s) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// exclusive scan of one int per thread over the block; returns this thread's prefix and
-// the block total through `total`
-__device__ inline int block_excl_scan(int v, int* wave_tot, int& total) {
+// exclusive scan over the block of two counts per thread, packed into one 64-bit value
+// (high word, low word); returns this thread's prefix and the block total through `total`
+__device__ inline uint64_t block_excl_scan(uint64_t v, uint64_t* wave_tot, uint64_t& total) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int inc = v;
+    uint64_t inc = v;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
-        const int n = __shfl_up(inc, o);
+        const uint64_t n = __shfl_up(inc, o);
         if (lane >= o) inc += n;
     }
     __syncthreads();                       // wave_tot may still be read from the last call
     if (lane == 63) wave_tot[wave] = inc;
     __syncthreads();
-    int before = 0;
+    uint64_t before = 0;
     total = 0;
 #pragma unroll
     for (int w = 0; w < TOPK_THREADS / 64; ++w) {
-        const int t = wave_tot[w];
+        const uint64_t t = wave_tot[w];
         if (w < wave) before += t;
         total += t;
     }
@@ -177,7 +220,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float* __restr
                                                             int32_t* __restrict__ idx,
                                                             int32_t* __restrict__ n_sel) {
     __shared__ int hist[256];
-    __shared__ int wave_tot[TOPK_THREADS / 64];
+    __shared__ uint64_t wave_tot[TOPK_THREADS / 64];
     __shared__ uint32_t sh_prefix;
     __shared__ int sh_need;
     const int64_t qi = blockIdx.x;
@@ -205,9 +248,9 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float* __restr
         __syncthreads();
         // bin b is chosen iff (#keys in bins above b) < need <= (#keys in bins >= b)
         const int mine = hist[tid];
-        int total;
-        const int below = block_excl_scan(mine, wave_tot, total);   // keys in bins < tid
-        const int above = total - below - mine;
+        uint64_t total;
+        const int below = (int)block_excl_scan((uint64_t)mine, wave_tot, total);   // keys in bins < tid
+        const int above = (int)total - below - mine;
         if (above < need && need <= above + mine) {
             sh_prefix = prefix | ((uint32_t)tid << shift);
             sh_need = need - above;
@@ -219,22 +262,32 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float* __restr
     }
     const uint32_t T = prefix;             // the k-th largest key; `need` of its copies are taken
 
-    int base_gt = 0, base_eq = 0;          // selected / equal frames before this sweep
-    for (int f0 = 0; f0 < n_frames; f0 += TOPK_THREADS) {
-        const int f = f0 + tid;
-        const uint32_t key = f < n_frames ? order_key(s[f]) : 0u;
-        const int gt = (f < n_frames && key > T) ? 1 : 0;
-        const int eq = (f < n_frames && key == T) ? 1 : 0;
-        int tot_gt, tot_eq;
-        const int pre_gt = block_excl_scan(gt, wave_tot, tot_gt);
-        const int pre_eq = block_excl_scan(eq, wave_tot, tot_eq);
-        const int eq_before = base_eq + pre_eq;
-        if (gt || (eq && eq_before < need)) {
-            const int eq_sel_before = eq_before < need ? eq_before : need;
-            out[base_gt + pre_gt + eq_sel_before] = f;
+    // ordered sweep: a thread owns SPAN consecutive frames, so one block scan orders 4096 frames
+    constexpr int SPAN = 16;
+    int base_gt = 0, base_eq = 0;          // frames above T / equal to T before this sweep
+    for (int f0 = 0; f0 < n_frames; f0 += TOPK_THREADS * SPAN) {
+        const int fa = f0 + tid * SPAN;
+        uint32_t gt_mask = 0, eq_mask = 0;
+#pragma unroll
+        for (int i = 0; i < SPAN; ++i)
+            if (fa + i < n_frames) {
+                const uint32_t key = order_key(s[fa + i]);
+                gt_mask |= (uint32_t)(key > T) << i;
+                eq_mask |= (uint32_t)(key == T) << i;
+            }
+        uint64_t tot;
+        const uint64_t pre = block_excl_scan(((uint64_t)__popc(gt_mask) << 32) | (uint64_t)__popc(eq_mask),
+                                             wave_tot, tot);
+        int n_gt = base_gt + (int)(pre >> 32), n_eq = base_eq + (int)(pre & 0xFFFFFFFFu);
+#pragma unroll
+        for (int i = 0; i < SPAN; ++i) {
+            const bool gt = (gt_mask >> i) & 1, eq = (eq_mask >> i) & 1;
+            if (gt || (eq && n_eq < need)) out[n_gt + (n_eq < need ? n_eq : need)] = fa + i;
+            n_gt += gt;
+            n_eq += eq;
         }
-        base_gt += tot_gt;
-        base_eq += tot_eq;
+        base_gt += (int)(tot >> 32);
+        base_eq += (int)(tot & 0xFFFFFFFFu);
     }
     if (tid == 0 && n_sel) n_sel[qi] = k;
 }
@@ -256,21 +309,30 @@ hipError_t frame_keys_launch(const void* k, int n_frames, int tokens_per_frame, 
 
 hipError_t retrieve_launch(const RetrieveArgs& a, hipStream_t stream) {
     const int d_prime = a.n_kv_heads * a.head_dim;
-    // token mean per query head: [n_questions, Hq * D] fp32 in a.q_vec
+    // token mean per query head: [n_questions, Hq * D] fp32, then the group mean: [n_questions, D']
     hipError_t e = frame_keys_launch(a.q_question, a.n_questions, a.n_q_tokens, a.n_q_heads * a.head_dim,
-                                     a.dtype, a.q_vec, stream);
+                                     a.dtype, a.q_heads, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(group_mean_kernel, dim3((unsigned)a.n_questions, (unsigned)((d_prime + 255) / 256)),
+                       dim3(256), 0, stream, a.q_heads, a.n_q_heads, a.n_kv_heads, a.head_dim, a.q_vec);
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
 
-    // questions per block: up to QB on a shared table, as many as fit 48 KB of LDS
-    int qb = a.frame_keys_stride ? 1 : QB;
-    while (qb > 1 && (size_t)qb * (d_prime + 1) * sizeof(float) > 48 * 1024) qb >>= 1;
-    int fblocks = (a.n_frames + SCORE_WAVES - 1) / SCORE_WAVES;
+    // Many questions on one table: 8 frames x 8 questions per wavefront (if 8 question vectors
+    // fit 48 KB of LDS).  One question per table: 4 frames per wavefront.
+    const bool batched = a.frame_keys_stride == 0 && a.n_questions > 1 &&
+                         (size_t)8 * (d_prime + 1) * sizeof(float) <= 48 * 1024;
+    const int fr = batched ? 8 : 4, qbt = batched ? 8 : 1;
+    int fblocks = (a.n_frames + SCORE_WAVES * fr - 1) / (SCORE_WAVES * fr);
     if (fblocks > 4096) fblocks = 4096;
-    dim3 sg((unsigned)fblocks, (unsigned)((a.n_questions + qb - 1) / qb));
-    const size_t lds = (size_t)qb * (d_prime + 1) * sizeof(float);
-    hipLaunchKernelGGL(score_kernel, sg, dim3(SCORE_WAVES * 64), lds, stream, a.frame_keys,
-                       a.frame_keys_stride, a.n_frames, a.n_q_heads, a.n_kv_heads, a.head_dim, a.q_vec,
-                       a.n_questions, qb, a.scores);
+    dim3 sg((unsigned)fblocks, (unsigned)((a.n_questions + qbt - 1) / qbt));
+    const size_t lds = (size_t)qbt * (d_prime + 1) * sizeof(float);
+    if (batched)
+        hipLaunchKernelGGL((score_kernel<8, 8>), sg, dim3(SCORE_WAVES * 64), lds, stream, a.frame_keys,
+                           a.frame_keys_stride, a.n_frames, d_prime, a.q_vec, a.n_questions, a.scores);
+    else
+        hipLaunchKernelGGL((score_kernel<4, 1>), sg, dim3(SCORE_WAVES * 64), lds, stream, a.frame_keys,
+                           a.frame_keys_stride, a.n_frames, d_prime, a.q_vec, a.n_questions, a.scores);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
 

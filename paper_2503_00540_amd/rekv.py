@@ -181,8 +181,10 @@ class Rekv:
             idx.data_ptr(), n_sel.data_ptr(), scores.data_ptr() if want_scores else None, _stream()))
         return idx, n_sel, scores
 
-    def gather_kv(self, src_k, src_v, idx, n_src_frames: int | None = None, dst_k=None, dst_v=None):
-        """idx [n_questions, k] int32 on the device.  src on the device, or pinned on the host."""
+    def gather_kv(self, src_k, src_v, idx, n_src_frames: int | None = None, dst_k=None, dst_v=None,
+                  host_mode: int = 2):
+        """idx [n_questions, k] int32 on the device.  src on the device, or pinned on the host
+        (host_mode 1: copy-engine copies per frame run, 2: the kernel reads host memory itself)."""
         kh = (self.n_kv_heads, self.head_dim)
         on_host = not src_k.is_cuda
         nf = src_k.shape[0] // self.tokens_per_frame if n_src_frames is None else n_src_frames
@@ -199,7 +201,7 @@ class Rekv:
         ps = (self._pinned(src_k, kh, "src_k"), self._pinned(src_v, kh, "src_v")) if on_host else \
              (self._dev(src_k, last=kh, name="src_k"), self._dev(src_v, last=kh, name="src_v"))
         self._check(self._lib.rekv_gather_kv(
-            self._h, ps[0], ps[1], 1 if on_host else 0, nf, self._dev(idx, torch.int32, name="idx"), nq, k,
+            self._h, ps[0], ps[1], host_mode if on_host else 0, nf, self._dev(idx, torch.int32, name="idx"), nq, k,
             self._dev(dst_k, name="dst_k"), self._dev(dst_v, name="dst_v"), _stream()))
         return dst_k, dst_v
 

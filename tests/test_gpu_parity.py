@@ -262,9 +262,10 @@ def test_gather_device_and_host_bit_exact():
     r.offload_kv(dk, dv, hk, hv, 10, 14)
     r.offload_wait()
     assert torch.equal(hk, dk.cpu()) and torch.equal(hv, dv.cpu())
-    gk_h, gv_h = r.gather_kv(hk, hv, idx)
-    torch.cuda.synchronize()
-    assert torch.equal(gk, gk_h) and torch.equal(gv, gv_h)
+    for mode in (1, 2):                                  # copy-engine path, zero-copy kernel path
+        gk_h, gv_h = r.gather_kv(hk, hv, idx, host_mode=mode)
+        torch.cuda.synchronize()
+        assert torch.equal(gk, gk_h) and torch.equal(gv, gv_h), mode
     nf = w.tokens_per_frame
     for qi in range(2):
         frames = [f for f in sel[qi] if f >= 0]
@@ -275,7 +276,13 @@ def test_gather_device_and_host_bit_exact():
         assert float(gk[qi, n:].abs().max() if n < gk.shape[1] else 0) == 0     # skipped slots are zero
     bad = torch.tensor([[0, 99]], dtype=torch.int32, device=DEV)
     with pytest.raises(RekvError, match="INVALID_ARG"):
-        r.gather_kv(hk, hv, bad)
+        r.gather_kv(hk, hv, bad, host_mode=1)
+    zk, _ = r.gather_kv(hk, hv, bad, host_mode=2)        # the kernel paths skip what is out of range
+    torch.cuda.synchronize()
+    assert torch.equal(zk[0, :nf], dk[:nf]) and float(zk[0, nf:].abs().max()) == 0
+    with pytest.raises(RekvError, match="pinned"):
+        r._check(r._lib.rekv_gather_kv(r._h, dk.cpu().data_ptr(), dk.cpu().data_ptr(), 2, 24, idx.data_ptr(),
+                                       2, 5, gk.data_ptr(), gv.data_ptr(), None))
 
 
 # ----------------------------------------------------------------------------------------
