@@ -360,6 +360,14 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
             for (int db = 0; db < D / 32; ++db)
                 o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[g16][db], pf, o[db], 0, 0, 0);
         }
+        // Order asked of the scheduler for the part above: one MFMA, then its share of the vector
+        // work (and, in the first half, one of the second V group's LDS reads).
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i < 8) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+        }
         __builtin_amdgcn_s_setprio(0);
         step_barrier<2 * DMA_PER_STEP>();   // the loads of this step and the one before may be in flight
     };
