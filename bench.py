@@ -5,7 +5,11 @@ question: sliding-window encode of every chunk (one multi-chunk launch), the fra
 retrieval (pool + cosine + top-k), the KV gather and the QA attention.  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C0..C4] [--no-cpu-baseline] [--streaming]
+
+The default workload is C1, the configuration the metric is quoted on; C2 (hour-long stream, KV
+offloaded to pinned host memory), C3 (28 layers) and C4 (64 concurrent questions) run the same
+step at their shapes, for the bandwidth-bound kernels' HBM fractions.
 """
 from __future__ import annotations
 
@@ -23,9 +27,9 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_FP32_VALU_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# HBM traffic of one encode launch at C1 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (see profiles/); None until measured for the workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes of one encode launch from rocprofv3 --pmc FETCH_SIZE (x 2.0) and
+# WRITE_SIZE (x 1.0), KiB per dispatch; profiles/attn_bf16_encode_C1_hbm_traffic.txt
+MEASURED_TRAFFIC_BYTES = {"C1-7B-1layer": int((2.0 * 266784 + 351460) * 1024)}
 
 
 def encode_flops(w) -> float:
@@ -85,13 +89,71 @@ def cpu_baseline(w, seconds_target=12.0):
             "encode_s": t_enc, "retrieval_qa_s": t_qa}
 
 
+def host_inputs(w, torch, np):
+    """C0 / C1: the seeded host generator of workloads.py (the arrays the parity tests use)."""
+    from paper_2503_00540_amd import workloads as W
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+    def dev(x):
+        return torch.from_numpy(np.ascontiguousarray(x)).to(tdt).to("cuda:0")
+
+    def cat(fn):
+        return torch.cat([dev(fn(w, f, min(f + 64, w.n_frames))) for f in range(0, w.n_frames, 64)])
+
+    qs = [W.question_qkv(w, i) for i in range(w.n_questions)]
+    planted = [W.planted_frames(w, i).tolist() for i in range(w.n_questions)]
+    return {"q": [cat(W.frames_q)], "k": [cat(W.frames_k)], "v": [cat(W.frames_v)],
+            "qq": dev(np.stack([x[0] for x in qs])), "qk": dev(np.stack([x[1] for x in qs])),
+            "qv": dev(np.stack([x[2] for x in qs])), "planted": planted}
+
+
+def gpu_inputs(w, torch):
+    """C2 / C3 / C4: the same recipe (N(0,1) + per-frame offset of sigma 0.5; question queries =
+    planted frames' key offsets + N(0, 0.3^2)) drawn on the GPU with torch's seeded generator -
+    these streams are too long to draw on the host within the run.  Q is kept for two layers
+    and reused alternately; every layer has its own K/V, as it would in HBM."""
+    g = torch.Generator(device="cuda:0").manual_seed(w.seed)
+    gc = torch.Generator().manual_seed(w.seed)
+    F, nf, G = w.n_frames, w.tokens_per_frame, w.group
+
+    def stream(heads):
+        out = torch.empty((F * nf, heads, w.head_dim), dtype=torch.bfloat16, device="cuda:0")
+        off = 0.5 * torch.randn((F, 1, heads, w.head_dim), device="cuda:0", generator=g)
+        for f in range(0, F, 128):
+            f1 = min(f + 128, F)
+            x = torch.randn((f1 - f, nf, heads, w.head_dim), device="cuda:0", generator=g) + off[f:f1]
+            out[f * nf:f1 * nf] = x.reshape(-1, heads, w.head_dim).to(torch.bfloat16)
+        return out, off[:, 0]
+
+    d = {"q": [stream(w.n_q_heads)[0] for _ in range(min(2, w.n_layers))], "k": [], "v": [],
+         "qq": [], "qk": [], "qv": [], "planted": []}
+    for layer in range(w.n_layers):
+        k, off_k = stream(w.n_kv_heads)
+        d["k"].append(k)
+        d["v"].append(stream(w.n_kv_heads)[0])
+        for _ in range(w.n_questions):
+            p = torch.randperm(F, generator=gc)[:w.n_planted].sort().values
+            d["planted"].append(p.tolist())
+            base = off_k[p.to("cuda:0")][torch.arange(w.n_q_tokens, device="cuda:0") % w.n_planted]   # [N_q, Hkv, D]
+            qq = base.repeat_interleave(G, dim=1) + 0.3 * torch.randn((w.n_q_tokens, w.n_q_heads, w.head_dim),
+                                                                      device="cuda:0", generator=g)
+            d["qq"].append(qq.to(torch.bfloat16))
+            d["qk"].append(torch.randn((w.n_q_tokens, w.n_kv_heads, w.head_dim), device="cuda:0", generator=g).to(torch.bfloat16))
+            d["qv"].append(torch.randn((w.n_q_tokens, w.n_kv_heads, w.head_dim), device="cuda:0", generator=g).to(torch.bfloat16))
+    for key in ("qq", "qk", "qv"):
+        d[key] = torch.stack(d[key])
+    return d
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C1")
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3", "C4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streaming", action="store_true",
+                    help="also time the stream encoded one launch per chunk (extra launches in a trace)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (one MI355X runs the whole path); "
@@ -104,102 +166,125 @@ def main() -> None:
     from paper_2503_00540_amd.rekv import Rekv
 
     w = W.CONFIGS[args.workload]
-    if w.n_layers != 1 or w.kv_on_host:
-        sys.exit("bench.py times single-layer, HBM-resident workloads (C0, C1, C4)")
+    big = args.workload in ("C2", "C3", "C4")
+    steps = args.steps if args.steps is not None else (3 if big else 20)
+    warmup = args.warmup if args.warmup is not None else (1 if big else 3)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     torch.cuda.set_device(0)
     r = Rekv.for_workload(w)
+    d = gpu_inputs(w, torch) if big else host_inputs(w, torch, np)     # resident in HBM before timing
 
-    def dev(x):
-        return torch.from_numpy(np.ascontiguousarray(x)).to(tdt).to("cuda:0")
-
-    # inputs: seeded, generated frame by frame on the host, resident in HBM before timing
-    step = 64
-    dq = torch.cat([dev(W.frames_q(w, f, min(f + step, w.n_frames))) for f in range(0, w.n_frames, step)])
-    dk = torch.cat([dev(W.frames_k(w, f, min(f + step, w.n_frames))) for f in range(0, w.n_frames, step)])
-    dv = torch.cat([dev(W.frames_v(w, f, min(f + step, w.n_frames))) for f in range(0, w.n_frames, step)])
-    qs = [W.question_qkv(w, i) for i in range(w.n_questions)]
-    q_q, q_k, q_v = (dev(np.stack([x[j] for x in qs])) for j in range(3))
-    n_chunks = w.n_frames // w.chunk_frames
+    L, nq, F, nf = w.n_layers, w.n_questions, w.n_frames, w.tokens_per_frame
+    n_chunks = F // w.chunk_frames
     d_prime = w.d_prime
-    out = torch.empty_like(dq)
-    fk = torch.empty((w.n_frames, d_prime), dtype=torch.float32, device="cuda:0")
-    ret_shape = (w.n_questions, w.top_k * w.tokens_per_frame, w.n_kv_heads, w.head_dim)
+    out = torch.empty_like(d["q"][0])
+    fk = torch.empty((L, F, d_prime), dtype=torch.float32, device="cuda:0")
+    ret_shape = (L * nq, w.top_k * nf, w.n_kv_heads, w.head_dim)
     gk, gv = torch.empty(ret_shape, dtype=tdt, device="cuda:0"), torch.empty(ret_shape, dtype=tdt, device="cuda:0")
-    qa_out = torch.empty_like(q_q)
+    qa_out = torch.empty_like(d["qq"])
+    hk = hv = None
+    if w.kv_on_host:
+        hk = torch.empty(d["k"][0].shape, dtype=tdt, pin_memory=True)
+        hv = torch.empty(d["v"][0].shape, dtype=tdt, pin_memory=True)
 
-    names = ["encode", "frame_keys", "retrieve", "gather", "qa"]
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(args.steps)]
+    names = ["encode", "frame_keys", "offload_issue", "offload_wait", "retrieve", "gather", "qa"]
 
-    def one_step(ev=None):
-        if ev: ev[0].record()
-        r.encode_chunk(dq, dk, dv, 0, w.l_x, n_chunks, w.l_l, out=out)
-        if ev: ev[1].record()
-        r.frame_keys(dk, w.n_frames, out=fk)
-        if ev: ev[2].record()
-        idx, _, _ = r.retrieve_topk(fk, w.n_frames, q_q, w.top_k)
-        if ev: ev[3].record()
-        r.gather_kv(dk, dv, idx, dst_k=gk, dst_v=gv)
-        if ev: ev[4].record()
-        r.qa_attention(q_q, gk, gv, q_k, q_v, out=qa_out)
-        if ev: ev[5].record()
+    def one_step(log=None):
+        def rec(name):
+            if log is not None:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()
+                log.append((name, e))
+        for layer in range(L):
+            rec("encode")
+            r.encode_chunk(d["q"][layer % len(d["q"])], d["k"][layer], d["v"][layer], 0, w.l_x, n_chunks, w.l_l, out=out)
+            rec("frame_keys")
+            r.frame_keys(d["k"][layer], F, out=fk[layer])
+            if w.kv_on_host:           # the encoded KV leaves HBM on the side stream while the path goes on
+                rec("offload_issue")
+                r.offload_kv(d["k"][layer], d["v"][layer], hk, hv, 0, F)
+        if w.kv_on_host:               # the question arrives once the stream's KV has left HBM
+            rec("offload_wait")
+            r.offload_wait()
+        rec("retrieve")
+        idx, _, _ = r.retrieve_topk(fk, F, d["qq"], w.top_k, frame_keys_stride=F * d_prime if L > 1 else 0)
+        for layer in range(L):
+            rec("gather")
+            src = (hk, hv) if w.kv_on_host else (d["k"][layer], d["v"][layer])
+            r.gather_kv(src[0], src[1], idx[layer * nq:(layer + 1) * nq], n_src_frames=F,
+                        dst_k=gk[layer * nq:(layer + 1) * nq], dst_v=gv[layer * nq:(layer + 1) * nq])
+        rec("qa")
+        r.qa_attention(d["qq"], gk, gv, d["qk"], d["qv"], out=qa_out)
+        rec(None)
         return idx
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         one_step()
     torch.cuda.synchronize()
+    logs = [[] for _ in range(steps)]
     t0 = time.perf_counter()
-    for s in range(args.steps):
-        idx = one_step(evs[s])
+    for s in range(steps):
+        idx = one_step(logs[s])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    ms = {n: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, n in enumerate(names)}
-    ms_per_step = elapsed / args.steps * 1e3
-    tokens_per_s = w.n_tokens / (elapsed / args.steps)
+    ms = {n: 0.0 for n in names}
+    for log in logs:
+        for (name, e0), (_, e1) in zip(log[:-1], log[1:]):
+            ms[name] += e0.elapsed_time(e1) / steps
+    ms_per_step = elapsed / steps * 1e3
+    n_tokens = L * w.n_tokens
+    tokens_per_s = n_tokens / (elapsed / steps)
 
     # the same stream encoded chunk by chunk (one launch per chunk, as a live stream arrives)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for c in range(n_chunks):
-        r.encode_chunk(dq[c * w.l_x:(c + 1) * w.l_x], dk, dv, c * w.l_x, w.l_x, 1, w.l_l,
-                       out=out[c * w.l_x:(c + 1) * w.l_x])
-    torch.cuda.synchronize()
-    streaming_s = time.perf_counter() - t1
+    streaming_s = None
+    if args.streaming:
+        dq, dk, dv = d["q"][0], d["k"][0], d["v"][0]
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for c in range(n_chunks):
+            r.encode_chunk(dq[c * w.l_x:(c + 1) * w.l_x], dk, dv, c * w.l_x, w.l_x, 1, w.l_l,
+                           out=out[c * w.l_x:(c + 1) * w.l_x])
+        torch.cuda.synchronize()
+        streaming_s = time.perf_counter() - t1
 
-    planted = [set(W.planted_frames(w, i).tolist()) <= set(idx[i].tolist()) for i in range(w.n_questions)]
-    fl = encode_flops(w)
+    planted = [set(p) <= set(idx[i].tolist()) for i, p in enumerate(d["planted"])]
+    fl = encode_flops(w)                                   # one launch = one layer's stream
     if w.dtype == "bf16":
         bound, peak = "mfma", PEAK_BF16_TFLOPS
     else:
         bound, peak = "alu", PEAK_FP32_VALU_TFLOPS
-    achieved = fl / (ms["encode"] * 1e-3) / 1e12
+    enc_launch_ms = ms["encode"] / L
+    achieved = fl / (enc_launch_ms * 1e-3) / 1e12
     es = 2 if w.dtype == "bf16" else 4
-    gather_bytes = 2 * 2 * w.n_questions * w.top_k * w.tokens_per_frame * d_prime * es   # K and V, read + write
-    fk_bytes = w.n_tokens * d_prime * es + w.n_frames * d_prime * 4
+    gather_bytes = 2 * L * nq * w.top_k * nf * d_prime * es          # K and V, read once (and written once)
+    fk_bytes = L * (w.n_tokens * d_prime * es + F * d_prime * 4)
     result = {
         "metric": "video tokens/s encoded (windowed attn, MFMA %); retrieval+QA latency ms (HBM GB/s)",
-        "value": tokens_per_s, "unit": "video tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "value": tokens_per_s, "unit": "video tokens/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.n_frames} frames x {w.tokens_per_frame} tokens, "
+        "config": {"workload": f"{w.name}: {L} layer(s), {F} frames x {nf} tokens, "
                                f"Hq/Hkv/D {w.n_q_heads}/{w.n_kv_heads}/{w.head_dim}, chunk {w.l_x} tokens, "
-                               f"window {w.l_l} tokens, {w.n_questions} question(s) of {w.n_q_tokens} tokens, "
-                               f"top-k {w.top_k}; one layer; a step = encode all {n_chunks} chunks in one "
-                               f"launch + frame vectors + retrieval + gather + QA attention",
+                               f"window {w.l_l} tokens, {nq} question(s) of {w.n_q_tokens} tokens, "
+                               f"top-k {w.top_k}, KV {'offloaded to pinned host memory' if w.kv_on_host else 'in HBM'}; "
+                               f"a step = per layer: encode all {n_chunks} chunks in one launch + frame vectors"
+                               f"{' + KV offload' if w.kv_on_host else ''}; then retrieval + gather + QA attention",
                    "n_chunks_per_launch": n_chunks},
-        "roofline": {"bound": bound, "kernel": "attn_bf16_kernel (rekv_encode_chunk)" if w.dtype == "bf16"
+        "roofline": {"bound": bound, "kernel": "attn_bf16_kernel<D, true> (rekv_encode_chunk)" if w.dtype == "bf16"
                      else "attn_f32_kernel (rekv_encode_chunk)",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
-                     "algorithmic_flop_per_launch": fl, "avg_launch_ms": ms["encode"]},
+                     "algorithmic_flop_per_launch": fl, "avg_launch_ms": enc_launch_ms},
         "kernel_ms": ms,
         "retrieval_qa_latency_ms": ms["retrieve"] + ms["gather"] + ms["qa"],
-        "encode_only_tokens_per_s": w.n_tokens / (ms["encode"] * 1e-3),
-        "streaming_tokens_per_s": w.n_tokens / streaming_s,
-        "hbm": {"gather_GBs": gather_bytes / (ms["gather"] * 1e-3) / 1e9,
+        "encode_only_tokens_per_s": n_tokens / (ms["encode"] * 1e-3),
+        "streaming_tokens_per_s": w.n_tokens / streaming_s if streaming_s else None,
+        "hbm": {("gather_host_link_GBs" if w.kv_on_host else "gather_read_plus_write_GBs"):
+                (1 if w.kv_on_host else 2) * gather_bytes / (ms["gather"] * 1e-3) / 1e9,
                 "frame_keys_GBs": fk_bytes / (ms["frame_keys"] * 1e-3) / 1e9,
-                "qa_TFLOPs": qa_flops(w) / (ms["qa"] * 1e-3) / 1e12, "peak_GBs": PEAK_HBM_GBS},
+                "retrieve_table_GBs": L * F * d_prime * 4 / (ms["retrieve"] * 1e-3) / 1e9,
+                "qa_TFLOPs": L * qa_flops(w) / (ms["qa"] * 1e-3) / 1e12, "peak_GBs": PEAK_HBM_GBS},
         "planted_frames_retrieved": all(planted),
     }
     if not args.no_cpu_baseline:

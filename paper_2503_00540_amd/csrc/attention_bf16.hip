@@ -124,14 +124,17 @@ __device__ inline void step_barrier() {
 template <int I>
 using IC = std::integral_constant<int, I>;
 
-template <int D>
+// ENCODE selects the segment layout (Eq. 1 window + chunk in one cache, or Eq. 3 retrieved KV +
+// question) at compile time; the two instantiations also show up under separate names in a trace.
+template <int D, bool ENCODE>
 __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     typedef Cfg<D> C;
     // K stages 0..3, then V stages 0..3; one array so that every stage is a constant offset
     __shared__ __attribute__((aligned(1024))) bf16_t lds[2 * STAGES * C::TILE_ELEMS];
     constexpr uint32_t TILE_B = C::TILE_ELEMS * 2;           // bytes per stage
 
-    const AttnProblem& p = a.p;
+    AttnProblem p = a.p;
+    p.is_encode = ENCODE;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hh = lane >> 5;
@@ -508,7 +511,10 @@ hipError_t launch(const AttnProblem& p, const AttnPlan& plan, void* workspace, h
         a.part_ml = a.part_o + ik * plan.n_splits * plan.m_tiles * BM * (int64_t)D;
     }
     const int64_t nb = ik * plan.n_splits * plan.m_tiles;
-    hipLaunchKernelGGL(attn_bf16_kernel<D>, dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
+    if (p.is_encode)
+        hipLaunchKernelGGL((attn_bf16_kernel<D, true>), dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
+    else
+        hipLaunchKernelGGL((attn_bf16_kernel<D, false>), dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (plan.n_splits > 1) {

@@ -20,27 +20,29 @@ __device__ inline float wave_sum(float v) {
 
 // ---------------------------------------------------------------------------------------
 // Frame vectors: v_f = (1/N_f) sum_j k_{f,j}, heads concatenated.
-// Block = 16 row groups x 16 column lanes; a column lane owns 16 bytes of the key row
-// (8 bf16 or 4 fp32).  grid = (frames, column blocks).
+// One workgroup streams one frame (a contiguous N_f x D' block) front to back: LPR lanes
+// cover a key row with 16-byte loads (8 bf16 or 4 fp32 each), the 256 / LPR row groups take
+// alternate rows, eight loads are in flight per thread, and the row groups' partial sums
+// meet in LDS.  Rows wider than 256 lanes are split over blockIdx.y.
 // ---------------------------------------------------------------------------------------
 template <bool BF16>
 __global__ __launch_bounds__(256) void frame_keys_kernel(const void* __restrict__ k, int n_f,
-                                                         int d_prime, float* __restrict__ out) {
+                                                         int d_prime, int lpr_log2,
+                                                         float* __restrict__ out) {
     constexpr int VEC = BF16 ? 8 : 4;
-    __shared__ float red[16][16 * VEC + 1];
-    const int cl = threadIdx.x & 15, rg = threadIdx.x >> 4;
-    const int col = (blockIdx.y * 16 + cl) * VEC;
+    constexpr int ES = BF16 ? 2 : 4;
+    __shared__ float red[256 * VEC];
+    const int lpr = 1 << lpr_log2, n_rg = 256 >> lpr_log2;
+    const int cl = threadIdx.x & (lpr - 1), rg = threadIdx.x >> lpr_log2;
+    const int col = (blockIdx.y * lpr + cl) * VEC;
     const int64_t frame = blockIdx.x;
     float acc[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
     if (col < d_prime) {
-        const char* base = static_cast<const char*>(k) +
-            ((frame * n_f) * (int64_t)d_prime + col) * (BF16 ? 2 : 4);
-        const int64_t pitch = (int64_t)d_prime * (BF16 ? 2 : 4);
-#pragma unroll 4
-        for (int j = rg; j < n_f; j += 16) {
-            const u32x4 w = *reinterpret_cast<const u32x4*>(base + j * pitch);
+        const char* base = static_cast<const char*>(k) + ((frame * n_f) * (int64_t)d_prime + col) * ES;
+        const int64_t pitch = (int64_t)d_prime * ES;
+        auto add = [&](const u32x4& w) {
             if (BF16) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -51,18 +53,27 @@ __global__ __launch_bounds__(256) void frame_keys_kernel(const void* __restrict_
 #pragma unroll
                 for (int i = 0; i < 4; ++i) acc[i] += __uint_as_float(w[i]);
             }
+        };
+        constexpr int U = 8;
+        int j = rg;
+        for (; j + n_rg * (U - 1) < n_f; j += n_rg * U) {
+            u32x4 w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) w[u] = *reinterpret_cast<const u32x4*>(base + (j + n_rg * u) * pitch);
+#pragma unroll
+            for (int u = 0; u < U; ++u) add(w[u]);
         }
+        for (; j < n_f; j += n_rg) add(*reinterpret_cast<const u32x4*>(base + j * pitch));
     }
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) red[rg][cl * VEC + i] = acc[i];
+    for (int i = 0; i < VEC; ++i) red[(rg * lpr + cl) * VEC + i] = acc[i];
     __syncthreads();
-    // 16*VEC columns, summed over the 16 row groups by the first 16*VEC threads
-    if (threadIdx.x < 16 * VEC) {
-        float s = 0.f;
-#pragma unroll
-        for (int g = 0; g < 16; ++g) s += red[g][threadIdx.x];
-        const int c = blockIdx.y * 16 * VEC + threadIdx.x;
-        if (c < d_prime) out[frame * d_prime + c] = s / (float)n_f;
+    // lpr * VEC columns, summed over the row groups
+    for (int c = threadIdx.x; c < lpr * VEC; c += 256) {
+        float sum = 0.f;
+        for (int g = 0; g < n_rg; ++g) sum += red[g * lpr * VEC + c];
+        const int oc = blockIdx.y * lpr * VEC + c;
+        if (oc < d_prime) out[frame * d_prime + oc] = sum / (float)n_f;
     }
 }
 
@@ -297,13 +308,16 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float* __restr
 hipError_t frame_keys_launch(const void* k, int n_frames, int tokens_per_frame, int d_prime,
                              int dtype, float* frame_keys, hipStream_t stream) {
     const int vec = dtype == REKV_BF16 ? 8 : 4;
-    dim3 grid((unsigned)n_frames, (unsigned)((d_prime + 16 * vec - 1) / (16 * vec)));
+    const int lanes = (d_prime + vec - 1) / vec;          // 16-byte lanes per key row
+    int lpr_log2 = 0;
+    while ((1 << lpr_log2) < lanes && lpr_log2 < 8) ++lpr_log2;
+    dim3 grid((unsigned)n_frames, (unsigned)((lanes + (1 << lpr_log2) - 1) >> lpr_log2));
     if (dtype == REKV_BF16)
         hipLaunchKernelGGL(frame_keys_kernel<true>, grid, dim3(256), 0, stream, k, tokens_per_frame,
-                           d_prime, frame_keys);
+                           d_prime, lpr_log2, frame_keys);
     else
         hipLaunchKernelGGL(frame_keys_kernel<false>, grid, dim3(256), 0, stream, k, tokens_per_frame,
-                           d_prime, frame_keys);
+                           d_prime, lpr_log2, frame_keys);
     return hipGetLastError();
 }
 
