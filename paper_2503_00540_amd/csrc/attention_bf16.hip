@@ -115,7 +115,7 @@ __device__ inline float pair_sum(float v) {
 
 template <int N>
 __device__ inline void step_barrier() {
-    static_assert(N >= 0 && N < 16, "vmcnt immediate");
+    static_assert(N >= 0 && N < 64, "vmcnt immediate");
     __builtin_amdgcn_sched_barrier(0);     // nothing of this step sinks below its barrier
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
     __builtin_amdgcn_sched_barrier(0);
