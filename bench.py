@@ -145,6 +145,41 @@ def gpu_inputs(w, torch):
     return d
 
 
+PROBE_COPY_BYTES = 1 << 30
+
+
+def box_peaks(r, torch, copy_only=False):
+    """What this GPU sustains: a plain streaming copy (bytes read + written per second) and a
+    register-resident bf16 MFMA loop.  Context for the roofline fractions, which stay priced
+    against the published peaks."""
+    src = torch.empty(PROBE_COPY_BYTES, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty_like(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    t_copy = timed(lambda: r.probe_copy(dst, src), 5)
+    out = {"copy_bytes": PROBE_COPY_BYTES, "copy_read_plus_write_GBs": 2 * PROBE_COPY_BYTES / t_copy / 1e9}
+    if not copy_only:
+        n_wg, n_it = 2048, 20000
+        sink = torch.empty(n_wg * 256, dtype=torch.float32, device="cuda:0")
+        flop = [0.0]
+
+        def mf():
+            flop[0] = r.probe_mfma(sink, n_wg, n_it)
+        t_mfma = timed(mf, 3)
+        out["mfma_bf16_loop_TFLOPs"] = flop[0] / t_mfma / 1e12
+    return out
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -154,6 +189,8 @@ def main() -> None:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streaming", action="store_true",
                     help="also time the stream encoded one launch per chunk (extra launches in a trace)")
+    ap.add_argument("--probe-copy-only", action="store_true",
+                    help="run only the known-size copy kernel (the calibration run of the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (one MI355X runs the whole path); "
@@ -172,6 +209,9 @@ def main() -> None:
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     torch.cuda.set_device(0)
     r = Rekv.for_workload(w)
+    if args.probe_copy_only:
+        print(json.dumps({"box_peaks": box_peaks(r, torch, copy_only=True)}))
+        return
     d = gpu_inputs(w, torch) if big else host_inputs(w, torch, np)     # resident in HBM before timing
 
     L, nq, F, nf = w.n_layers, w.n_questions, w.n_frames, w.tokens_per_frame
@@ -286,6 +326,7 @@ def main() -> None:
                 "retrieve_table_GBs": L * F * d_prime * 4 / (ms["retrieve"] * 1e-3) / 1e9,
                 "qa_TFLOPs": L * qa_flops(w) / (ms["qa"] * 1e-3) / 1e12, "peak_GBs": PEAK_HBM_GBS},
         "planted_frames_retrieved": all(planted),
+        "box_peaks": box_peaks(r, torch),
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w)

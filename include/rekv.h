@@ -174,6 +174,23 @@ rekv_status rekv_offload_kv(rekv_ctx* ctx, const void* dev_k, const void* dev_v,
                             void* host_v, int64_t first_frame, int32_t n_frames, void* stream);
 rekv_status rekv_offload_wait(rekv_ctx* ctx);
 
+/*
+ * Measurement probes.  They are not operations of the method: they show what this GPU
+ * sustains on the two resources the path is priced against, so that a kernel's rate can be
+ * read against the machine it ran on as well as against the published peaks.
+ *
+ * rekv_probe_copy: plain streaming copy of n_bytes (a multiple of 16; both pointers 16-byte
+ *   aligned, device memory, not overlapping).  Moves n_bytes in and n_bytes out of HBM; it
+ *   is also the kernel of known size that the HBM byte counters are calibrated on.
+ * rekv_probe_mfma: n_workgroups workgroups of 4 wavefronts, each wavefront issuing
+ *   4 * n_iters independent-chain bf16 32x32x16 MFMAs from registers.  sink receives
+ *   n_workgroups * 256 floats (so the work is not optimised away); *flop (host pointer, may
+ *   be NULL) receives the floating-point operations of the launch.
+ */
+rekv_status rekv_probe_copy(rekv_ctx* ctx, void* dst, const void* src, int64_t n_bytes, void* stream);
+rekv_status rekv_probe_mfma(rekv_ctx* ctx, float* sink, int32_t n_workgroups, int32_t n_iters,
+                            double* flop, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

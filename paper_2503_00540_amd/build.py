@@ -12,7 +12,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "librekv.so")
-SOURCES = ["api.hip", "attention_bf16.hip", "attention_f32.hip", "retrieval.hip", "gather.hip"]
+SOURCES = ["api.hip", "attention_bf16.hip", "attention_f32.hip", "retrieval.hip", "gather.hip", "probe.hip"]
 
 # Packed-fp32 VALU instructions are switched off for all device code.
 HIPCC_FLAGS = [

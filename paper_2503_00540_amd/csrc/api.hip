@@ -335,4 +335,24 @@ rekv_status rekv_offload_wait(rekv_ctx* c) {
     return e == hipSuccess ? REKV_OK : fail_hip(c, "rekv_offload_wait", e);
 }
 
+rekv_status rekv_probe_copy(rekv_ctx* c, void* dst, const void* src, int64_t n_bytes, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!dst || !src) return fail(c, REKV_ERR_INVALID_ARG, "rekv_probe_copy: null pointer");
+    if (n_bytes <= 0 || n_bytes % 16 != 0 || (reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) % 16 != 0)
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_probe_copy: n_bytes=%lld and both pointers must be multiples of 16",
+                    (long long)n_bytes);
+    hipError_t e = rekv::launch_probe_copy(dst, src, n_bytes, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "rekv_probe_copy", e);
+}
+
+rekv_status rekv_probe_mfma(rekv_ctx* c, float* sink, int32_t n_workgroups, int32_t n_iters, double* flop, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!sink) return fail(c, REKV_ERR_INVALID_ARG, "rekv_probe_mfma: null pointer");
+    if (n_workgroups <= 0 || n_workgroups > (1 << 20) || n_iters <= 0 || n_iters > (1 << 24))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_probe_mfma: n_workgroups=%d n_iters=%d", n_workgroups, n_iters);
+    if (flop) *flop = rekv::probe_mfma_flop(n_workgroups, n_iters);
+    hipError_t e = rekv::launch_probe_mfma(sink, n_workgroups, n_iters, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "rekv_probe_mfma", e);
+}
+
 }  // extern "C"

@@ -86,4 +86,9 @@ hipError_t gather_launch(const void* src_k, const void* src_v, int n_src_frames,
                          int n_blocks, size_t frame_bytes, void* dst_k, void* dst_v,
                          hipStream_t stream);
 
+// Measurement probes (probe.hip).
+hipError_t launch_probe_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t stream);
+hipError_t launch_probe_mfma(float* sink, int32_t n_workgroups, int32_t n_iters, hipStream_t stream);
+double probe_mfma_flop(int32_t n_workgroups, int32_t n_iters);
+
 }  // namespace rekv

@@ -23,7 +23,7 @@ _DTYPES = {"f32": (REKV_F32, torch.float32), "bf16": (REKV_BF16, torch.bfloat16)
 # Every entry point include/rekv.h declares.
 SYMBOLS = ("rekv_create", "rekv_destroy", "rekv_last_error", "rekv_encode_chunk",
            "rekv_frame_keys", "rekv_retrieve_topk", "rekv_gather_kv", "rekv_qa_attention",
-           "rekv_offload_kv", "rekv_offload_wait")
+           "rekv_offload_kv", "rekv_offload_wait", "rekv_probe_copy", "rekv_probe_mfma")
 
 
 class RekvShape(ctypes.Structure):
@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
     L.rekv_offload_kv.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32,
                                   c_void_p]
     L.rekv_offload_wait.argtypes = [c_void_p]
+    L.rekv_probe_copy.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_void_p]
+    L.rekv_probe_mfma.argtypes = [c_void_p, c_void_p, c_int32, c_int32, POINTER(ctypes.c_double), c_void_p]
     for name in SYMBOLS[3:]:
         getattr(L, name).restype = c_int32
     _lib = L
@@ -240,3 +242,22 @@ class Rekv:
 
     def offload_wait(self):
         self._check(self._lib.rekv_offload_wait(self._h))
+
+    def probe_copy(self, dst: torch.Tensor, src: torch.Tensor) -> int:
+        """rekv_probe_copy: streaming copy of src into dst; returns the bytes copied."""
+        n_bytes = src.numel() * src.element_size()
+        if dst.numel() * dst.element_size() != n_bytes or not (dst.is_cuda and src.is_cuda):
+            raise ValueError("probe_copy: dst and src must be device tensors of the same byte size")
+        if not (dst.is_contiguous() and src.is_contiguous()):
+            raise ValueError("probe_copy: tensors must be contiguous")
+        self._check(self._lib.rekv_probe_copy(self._h, dst.data_ptr(), src.data_ptr(), n_bytes, _stream()))
+        return n_bytes
+
+    def probe_mfma(self, sink: torch.Tensor, n_workgroups: int, n_iters: int) -> float:
+        """rekv_probe_mfma: register-resident MFMA loop; returns the launch's flop count."""
+        if sink.dtype != torch.float32 or not sink.is_cuda or sink.numel() < n_workgroups * 256:
+            raise ValueError("probe_mfma: sink must be a device fp32 tensor of >= n_workgroups * 256 elements")
+        flop = ctypes.c_double(0.0)
+        self._check(self._lib.rekv_probe_mfma(self._h, sink.data_ptr(), n_workgroups, n_iters,
+                                              ctypes.byref(flop), _stream()))
+        return flop.value
