@@ -161,6 +161,36 @@ def qa_attention(q, k_ret, v_ret, k_self, v_self, scale=None, return_probs=False
     return (out, probs) if return_probs else out
 
 
+def decode_attention(q_new, k_ret, v_ret, k_text, v_text, scale=None):
+    """Eq. 3 for X = the token(s) being decoded: the context is the retrieved video KV
+    followed by the text KV so far (question, generated tokens, and the new tokens'
+    own keys and values, which are the last n_new rows of k_text / v_text).  New token
+    i attends to all of R and to the text tokens up to and including itself, i.e. to
+    text positions <= n_text - n_new + i.
+
+    q_new [n_new, Hq, D], k_ret / v_ret [n_ret, Hkv, D], k_text / v_text [n_text, Hkv, D]
+    with n_text >= n_new -> O [n_new, Hq, D].
+    """
+    q = _f64(q_new)
+    n_new, n_q_heads, d = q.shape
+    n_ret = np.asarray(k_ret).shape[0]
+    n_text = np.asarray(k_text).shape[0]
+    if n_text < n_new:
+        raise ValueError("the text KV must already hold the new tokens' own rows")
+    keys = np.concatenate([_f64(k_ret), _f64(k_text)])
+    vals = np.concatenate([_f64(v_ret), _f64(v_text)])
+    group = n_q_heads // keys.shape[1]
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    visible = np.ones((n_new, n_ret + n_text), dtype=bool)
+    for i in range(n_new):
+        visible[i, n_ret + (n_text - n_new + i) + 1:] = False
+    out = np.empty_like(q)
+    for h in range(n_q_heads):
+        out[:, h], _ = softmax_attention(q[:, h], keys[:, h // group], vals[:, h // group],
+                                         visible, scale)
+    return out
+
+
 def retrieve(frame_vecs, q_question, n_kv_heads, k, n_visible=None):
     """Internal retrieval for one question: pooled question vector, Eq. 2 scores over
     the frames seen before the question was asked (the question's timestamp cuts off

@@ -173,6 +173,42 @@ def test_qa_attention_against_library_and_invariants():
     np.testing.assert_allclose(got, enc, atol=1e-12)
 
 
+def test_decode_attention_against_library_and_prefill():
+    n_ret, n_text, Hq, Hkv, D = 13, 9, 6, 2, 8
+    kr, vr = _rand((n_ret, Hkv, D), 31), _rand((n_ret, Hkv, D), 32)
+    kt, vt = _rand((n_text, Hkv, D), 33), _rand((n_text, Hkv, D), 34)
+    qt = _rand((n_text, Hq, D), 35)
+    # library: decoding the last n_new tokens is the tail of a full causal attention over
+    # [R, text], for every split of the text into "already there" and "new"
+    full = _sdpa(np.concatenate([_rand((n_ret, Hq, D), 36), qt]), np.concatenate([kr, kt]),
+                 np.concatenate([vr, vt]), causal=True)[n_ret:]
+    for n_new in (1, 2, n_text):
+        got = O.decode_attention(qt[n_text - n_new:], kr, vr, kt, vt)
+        np.testing.assert_allclose(got, full[n_text - n_new:], atol=1e-12)
+    # one token with nothing masked: plain softmax attention over all keys, by hand
+    got = O.decode_attention(qt[-1:], kr, vr, kt, vt)
+    keys, vals = np.concatenate([kr, kt]), np.concatenate([vr, vt])
+    for h in range(Hq):
+        z = keys[:, h // 3] @ qt[-1, h] / math.sqrt(D)
+        w = np.exp(z - z.max())
+        np.testing.assert_allclose(got[0, h], (w / w.sum()) @ vals[:, h // 3], atol=1e-12)
+    # token-by-token decoding reproduces the prefill of the same tokens (Eq. 3, both cases of X)
+    prefill = O.qa_attention(qt, kr, vr, kt, vt)
+    for i in range(n_text):
+        step = O.decode_attention(qt[i:i + 1], kr, vr, kt[:i + 1], vt[:i + 1])
+        np.testing.assert_allclose(step[0], prefill[i], atol=1e-12)
+    # a later text token must not leak into an earlier new token
+    kt2, vt2 = kt.copy(), vt.copy()
+    kt2[-1] += 5.0
+    vt2[-1] -= 3.0
+    a = O.decode_attention(qt[-2:], kr, vr, kt, vt)
+    b = O.decode_attention(qt[-2:], kr, vr, kt2, vt2)
+    np.testing.assert_allclose(a[0], b[0], atol=1e-14)
+    assert np.abs(a[1] - b[1]).max() > 1e-3
+    with pytest.raises(ValueError):
+        O.decode_attention(qt[-3:], kr, vr, kt[:2], vt[:2])
+
+
 # ----------------------------------------------------------------------------------
 # frame vectors, question vector, Eq. 2 scores
 # ----------------------------------------------------------------------------------
