@@ -160,6 +160,24 @@ rekv_status rekv_qa_attention(rekv_ctx* ctx, const void* q, const void* k_ret, c
                               int32_t n_questions, int32_t n_q_tokens, void* out, void* stream);
 
 /*
+ * Answer decoding over the retrieved KV, Eq. 3 with X = the token(s) being decoded: the
+ * context is the retrieved KV followed by the text KV so far (question and generated
+ * tokens).  The caller has already appended the new tokens' own K/V, so they are the last
+ * n_new_tokens of the n_text_tokens valid text rows; new token i attends to every retrieved
+ * token and to text rows j <= n_text_tokens - n_new_tokens + i.  rekv_qa_attention is the
+ * case n_new_tokens = n_text_tokens = text_stride = N_q.
+ *
+ *   q, out          [n_questions, n_new_tokens, Hq, D]
+ *   k_ret, v_ret    [n_questions, n_ret_tokens, Hkv, D]   (n_ret_tokens may be 0)
+ *   k_text, v_text  [n_questions, text_stride, Hkv, D], the first n_text_tokens rows of each
+ *                   question valid (text_stride >= n_text_tokens >= n_new_tokens >= 1)
+ */
+rekv_status rekv_decode_attention(rekv_ctx* ctx, const void* q, const void* k_ret, const void* v_ret,
+                                  int32_t n_ret_tokens, const void* k_text, const void* v_text,
+                                  int64_t text_stride, int32_t n_text_tokens, int32_t n_questions,
+                                  int32_t n_new_tokens, void* out, void* stream);
+
+/*
  * Offload of encoded KV to RAM (the paper stores all video KV and moves what leaves the
  * local window off the GPU).  Copies n_frames whole frames of K and V, starting at frame
  * first_frame of the device arrays, to the same frame positions of the pinned host arrays.

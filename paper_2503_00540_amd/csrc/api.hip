@@ -152,7 +152,7 @@ rekv_status rekv_encode_chunk(rekv_ctx* c, const void* q, const void* k_cache, c
     memset(&p, 0, sizeof(p));
     p.q = q; p.out = out;
     p.k_a = k_cache; p.v_a = v_cache; p.k_b = k_cache; p.v_b = v_cache;
-    p.first_token = first_token; p.l_l = l_l; p.len_a = 0; p.len_b = l_x;
+    p.first_token = first_token; p.l_l = l_l; p.len_a = 0; p.len_b = l_x; p.len_q = l_x; p.b_stride = 0;
     p.n_items = n_chunks; p.is_encode = 1;
     p.n_q_heads = c->shape.n_q_heads; p.n_kv_heads = c->shape.n_kv_heads; p.head_dim = c->shape.head_dim;
     p.scale = c->scale;
@@ -176,7 +176,36 @@ rekv_status rekv_qa_attention(rekv_ctx* c, const void* q, const void* k_ret, con
     memset(&p, 0, sizeof(p));
     p.q = q; p.out = out;
     p.k_a = k_ret ? k_ret : k_self; p.v_a = v_ret ? v_ret : v_self; p.k_b = k_self; p.v_b = v_self;
-    p.first_token = 0; p.l_l = 0; p.len_a = n_ret_tokens; p.len_b = n_q_tokens;
+    p.first_token = 0; p.l_l = 0; p.len_a = n_ret_tokens; p.len_b = n_q_tokens; p.len_q = n_q_tokens;
+    p.b_stride = n_q_tokens;
+    p.n_items = n_questions; p.is_encode = 0;
+    p.n_q_heads = c->shape.n_q_heads; p.n_kv_heads = c->shape.n_kv_heads; p.head_dim = c->shape.head_dim;
+    p.scale = c->scale;
+    return run_attention(c, p, static_cast<hipStream_t>(stream));
+}
+
+rekv_status rekv_decode_attention(rekv_ctx* c, const void* q, const void* k_ret, const void* v_ret,
+                                  int32_t n_ret_tokens, const void* k_text, const void* v_text,
+                                  int64_t text_stride, int32_t n_text_tokens, int32_t n_questions,
+                                  int32_t n_new_tokens, void* out, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!q || !k_text || !v_text || !out || (n_ret_tokens > 0 && (!k_ret || !v_ret)))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_decode_attention: null pointer");
+    if (!aligned16(q) || !aligned16(k_ret) || !aligned16(v_ret) || !aligned16(k_text) || !aligned16(v_text) || !aligned16(out))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_decode_attention: pointers must be 16-byte aligned");
+    if (n_ret_tokens < 0 || n_questions <= 0 || n_new_tokens <= 0 || n_text_tokens < n_new_tokens ||
+        text_stride < n_text_tokens)
+        return fail(c, REKV_ERR_INVALID_ARG,
+                    "rekv_decode_attention: n_ret_tokens=%d n_questions=%d n_new_tokens=%d n_text_tokens=%d text_stride=%lld",
+                    n_ret_tokens, n_questions, n_new_tokens, n_text_tokens, (long long)text_stride);
+    if ((int64_t)n_new_tokens * (c->shape.n_q_heads / c->shape.n_kv_heads) > 0x3FFFFFFF)
+        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_decode_attention: %d new tokens are too many", n_new_tokens);
+    rekv::AttnProblem p;
+    memset(&p, 0, sizeof(p));
+    p.q = q; p.out = out;
+    p.k_a = k_ret ? k_ret : k_text; p.v_a = v_ret ? v_ret : v_text; p.k_b = k_text; p.v_b = v_text;
+    p.first_token = 0; p.l_l = 0; p.len_a = n_ret_tokens; p.len_b = n_text_tokens; p.len_q = n_new_tokens;
+    p.b_stride = text_stride;
     p.n_items = n_questions; p.is_encode = 0;
     p.n_q_heads = c->shape.n_q_heads; p.n_kv_heads = c->shape.n_kv_heads; p.head_dim = c->shape.head_dim;
     p.scale = c->scale;

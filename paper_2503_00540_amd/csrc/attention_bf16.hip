@@ -157,7 +157,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     const char* kb = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_b) + seg.b_off * row_stride + kvh * D);
     const char* vb = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.v_b) + seg.b_off * row_stride + kvh * D);
 
-    const int m_rows = p.len_b * G;
+    const int m_rows = p.len_q * G;
     const int m0 = mt * BM;
     const int row = m0 + wave * WM + col;        // this lane's query row
     const int tok = row / G;                      // its token inside the item
@@ -168,9 +168,10 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     const int tiles_a = (seg.len_a + BN - 1) / BN;
     const int a_full = seg.len_a / BN;
     const int tiles_b_all = (p.len_b + BN - 1) / BN;
+    const int q_pos0 = p.len_b - p.len_q;         // position of query token 0 inside segment B
     int last_tok = (m0 + BM - 1) / G;
-    if (last_tok > p.len_b - 1) last_tok = p.len_b - 1;
-    const int n_tiles = tiles_a + last_tok / BN + 1;
+    if (last_tok > p.len_q - 1) last_tok = p.len_q - 1;
+    const int n_tiles = tiles_a + (last_tok + q_pos0) / BN + 1;
     const int per_split = (tiles_a + tiles_b_all + a.n_splits - 1) / a.n_splits;
     const int t_begin = split * per_split;
     int t_end = t_begin + per_split;
@@ -240,7 +241,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     bf16x8 qf[D / 16];
     {
         const bf16_t* qrow = static_cast<const bf16_t*>(p.q) +
-            (((int64_t)item * p.len_b + tok) * p.n_q_heads + kvh * G + (row - tok * G)) * D;
+            (((int64_t)item * p.len_q + tok) * p.n_q_heads + kvh * G + (row - tok * G)) * D;
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) {
             u32x4 v = {0u, 0u, 0u, 0u};
@@ -313,7 +314,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
             const bool in_b = t >= tiles_a;
             const int key0 = (in_b ? t - tiles_a : t) * BN;
             if (in_b || key0 + BN > seg.len_a) {
-                const int lim = (in_b ? (tok + 1 < p.len_b ? tok + 1 : p.len_b) : seg.len_a) - key0;
+                const int lim = (in_b ? (tok + q_pos0 + 1 < p.len_b ? tok + q_pos0 + 1 : p.len_b) : seg.len_a) - key0;
 #pragma unroll
                 for (int j = 0; j < 16; ++j) {
                     const int key = (j >> 2) * 8 + hh * 4 + (j & 3);
@@ -426,7 +427,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
         if (row_ok) {
             const float inv = 1.f / l_tot;
             bf16_t* orow = static_cast<bf16_t*>(p.out) +
-                (((int64_t)item * p.len_b + tok) * p.n_q_heads + kvh * G + (row - tok * G)) * D;
+                (((int64_t)item * p.len_q + tok) * p.n_q_heads + kvh * G + (row - tok * G)) * D;
 #pragma unroll
             for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -465,7 +466,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(KernelArgs a) {
     const AttnProblem& p = a.p;
     constexpr int TPR = D / 4;                 // threads per row
     const int G = p.n_q_heads / p.n_kv_heads;
-    const int m_rows = p.len_b * G;
+    const int m_rows = p.len_q * G;
     const int64_t rows_pad = (int64_t)a.m_tiles * BM;
     const int r_in_block = threadIdx.x / TPR, dq = threadIdx.x % TPR;
     const int64_t gr = (int64_t)blockIdx.x * (256 / TPR) + r_in_block;   // over (item, kvh, row)
@@ -489,7 +490,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(KernelArgs a) {
     const float inv = 1.f / l_all;
     const int tok = row / G;
     bf16_t* orow = static_cast<bf16_t*>(p.out) +
-        (((int64_t)item * p.len_b + tok) * p.n_q_heads + kvh * G + (row - tok * G)) * D + dq * 4;
+        (((int64_t)item * p.len_q + tok) * p.n_q_heads + kvh * G + (row - tok * G)) * D + dq * 4;
     f32x2 lo = {acc[0] * inv, acc[1] * inv}, hi = {acc[2] * inv, acc[3] * inv};
     u32x2 w;
     w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
@@ -518,7 +519,7 @@ hipError_t launch(const AttnProblem& p, const AttnPlan& plan, void* workspace, h
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (plan.n_splits > 1) {
-        const int64_t rows = ik * p.len_b * (p.n_q_heads / p.n_kv_heads);
+        const int64_t rows = ik * p.len_q * (p.n_q_heads / p.n_kv_heads);
         const int rpb = 256 / (D / 4);
         hipLaunchKernelGGL(attn_merge_kernel<D>, dim3((unsigned)((rows + rpb - 1) / rpb)), dim3(256),
                            0, stream, a);
@@ -532,7 +533,7 @@ hipError_t launch(const AttnProblem& p, const AttnPlan& plan, void* workspace, h
 AttnPlan attn_bf16_plan(const AttnProblem& p) {
     AttnPlan plan;
     const int G = p.n_q_heads / p.n_kv_heads;
-    plan.m_tiles = (p.len_b * G + BM - 1) / BM;
+    plan.m_tiles = (p.len_q * G + BM - 1) / BM;
     const int64_t base = (int64_t)p.n_items * p.n_kv_heads * plan.m_tiles;
     // longest tile list of any item (encode: a full window; QA: all retrieved tokens)
     const int len_a_max = p.is_encode ? p.l_l : p.len_a;

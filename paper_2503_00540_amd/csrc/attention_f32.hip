@@ -30,7 +30,7 @@ __global__ __launch_bounds__(ROWS_PER_BLOCK * 64) void attn_f32_kernel(AttnProbl
     const int G = p.n_q_heads / p.n_kv_heads;
     const int item = blockIdx.y;
     const int64_t r = (int64_t)blockIdx.x * ROWS_PER_BLOCK + wave;   // over (token, head)
-    if (r >= (int64_t)p.len_b * p.n_q_heads) return;                 // whole wavefront leaves
+    if (r >= (int64_t)p.len_q * p.n_q_heads) return;                 // whole wavefront leaves
     const int tok = (int)(r / p.n_q_heads), h = (int)(r % p.n_q_heads), kvh = h / G;
     const ItemSegs seg = item_segments(p, item);
     const int64_t row_stride = (int64_t)p.n_kv_heads * D;
@@ -38,7 +38,7 @@ __global__ __launch_bounds__(ROWS_PER_BLOCK * 64) void attn_f32_kernel(AttnProbl
     const float* va = static_cast<const float*>(p.v_a) + seg.a_off * row_stride + kvh * D;
     const float* kb = static_cast<const float*>(p.k_b) + seg.b_off * row_stride + kvh * D;
     const float* vb = static_cast<const float*>(p.v_b) + seg.b_off * row_stride + kvh * D;
-    const int64_t qo = (((int64_t)item * p.len_b + tok) * p.n_q_heads + h) * D;
+    const int64_t qo = (((int64_t)item * p.len_q + tok) * p.n_q_heads + h) * D;
     const float* q = static_cast<const float*>(p.q) + qo;
     for (int d = lane; d < D; d += 64) q_lds[wave][d] = q[d];
     // q_lds[wave] and p_lds[wave] are private to this wavefront: wave-level ordering suffices
@@ -46,7 +46,7 @@ __global__ __launch_bounds__(ROWS_PER_BLOCK * 64) void attn_f32_kernel(AttnProbl
 
     float o[MAX_D / 64] = {0.f, 0.f, 0.f, 0.f};
     float m = -INFINITY, l = 0.f;
-    const int n_vis_b = tok + 1;                 // causal part: own tokens up to itself
+    const int n_vis_b = tok + (p.len_b - p.len_q) + 1;   // causal part: text tokens up to itself
     const int n_keys = seg.len_a + n_vis_b;
     for (int j0 = 0; j0 < n_keys; j0 += 64) {
         const int j = j0 + lane;
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(ROWS_PER_BLOCK * 64) void attn_f32_kernel(AttnProbl
 }  // namespace
 
 hipError_t attn_f32_launch(const AttnProblem& p, hipStream_t stream) {
-    const int64_t rows = (int64_t)p.len_b * p.n_q_heads;
+    const int64_t rows = (int64_t)p.len_q * p.n_q_heads;
     dim3 grid((unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), (unsigned)p.n_items);
     hipLaunchKernelGGL(attn_f32_kernel, grid, dim3(ROWS_PER_BLOCK * 64), 0, stream, p);
     return hipGetLastError();

@@ -12,11 +12,13 @@ typedef __bf16 bf16_t;
 
 // One attention problem family: every batch item (a chunk of the stream, or a question)
 // attends to two key segments.  Segment A is visible to every query row; segment B is the
-// item's own tokens, visible causally (query token i sees B-token j iff j <= i).
+// item's text tokens, visible causally: the len_q query tokens are the last len_q tokens of
+// B, so query token i sees B-token j iff j <= i + (len_b - len_q).
 //   encode (Eq. 1): A = local window in the cache, B = the chunk's own K/V in the cache
 //   QA     (Eq. 3): A = retrieved KV of the question, B = the question's own K/V
+//   decode (Eq. 3): A = retrieved KV, B = question + generated tokens, queries = the new ones
 struct AttnProblem {
-    const void* q;      // [n_items * len_b, Hq, D]
+    const void* q;      // [n_items * len_q, Hq, D]
     void* out;          // same shape
     const void* k_a;    // encode: k_cache; QA: k_ret
     const void* v_a;
@@ -25,7 +27,9 @@ struct AttnProblem {
     int64_t first_token;  // encode only
     int32_t l_l;          // encode only: window length in tokens
     int32_t len_a;        // QA only: retrieved tokens per question
-    int32_t len_b;        // l_x or N_q
+    int32_t len_b;        // l_x, N_q, or the text tokens so far
+    int32_t len_q;        // query tokens per item: len_b, or the new tokens of a decode step
+    int64_t b_stride;     // QA / decode: tokens between consecutive items' B segments
     int32_t n_items;      // chunks or questions
     int32_t is_encode;
     int32_t n_q_heads, n_kv_heads, head_dim;
@@ -47,7 +51,7 @@ __host__ __device__ inline ItemSegs item_segments(const AttnProblem& p, int item
         s.len_a = (int32_t)(t0 - w0);
     } else {
         s.a_off = (int64_t)item * p.len_a;
-        s.b_off = (int64_t)item * p.len_b;
+        s.b_off = (int64_t)item * p.b_stride;
         s.len_a = p.len_a;
     }
     return s;

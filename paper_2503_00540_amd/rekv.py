@@ -23,6 +23,7 @@ _DTYPES = {"f32": (REKV_F32, torch.float32), "bf16": (REKV_BF16, torch.bfloat16)
 # Every entry point include/rekv.h declares.
 SYMBOLS = ("rekv_create", "rekv_destroy", "rekv_last_error", "rekv_encode_chunk",
            "rekv_frame_keys", "rekv_retrieve_topk", "rekv_gather_kv", "rekv_qa_attention",
+           "rekv_decode_attention",
            "rekv_offload_kv", "rekv_offload_wait", "rekv_probe_copy", "rekv_probe_mfma")
 
 
@@ -64,6 +65,8 @@ def lib() -> ctypes.CDLL:
                                  c_int32, c_void_p, c_void_p, c_void_p]
     L.rekv_qa_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p,
                                     c_int32, c_int32, c_void_p, c_void_p]
+    L.rekv_decode_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p,
+                                        c_int64, c_int32, c_int32, c_int32, c_void_p, c_void_p]
     L.rekv_offload_kv.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32,
                                   c_void_p]
     L.rekv_offload_wait.argtypes = [c_void_p]
@@ -228,6 +231,30 @@ class Rekv:
             self._dev(v_ret, last=kh, name="v_ret") if n_ret else None, n_ret,
             self._dev(k_self, last=kh, name="k_self"), self._dev(v_self, last=kh, name="v_self"),
             nq, n_q_tokens, self._dev(out, last=qh, name="out"), _stream()))
+        return out
+
+    def decode_attention(self, q, k_ret, v_ret, k_text, v_text, n_text_tokens: int, out=None):
+        """q [n_questions, n_new, Hq, D]; k_ret/v_ret [n_questions, n_ret, Hkv, D]; k_text/v_text
+        [n_questions, text_stride, Hkv, D] whose first n_text_tokens rows are valid and end with
+        the new tokens' own K/V."""
+        qh, kh = (self.n_q_heads, self.head_dim), (self.n_kv_heads, self.head_dim)
+        if q.dim() != 4 or k_ret.dim() != 4 or k_text.dim() != 4:
+            raise ValueError("q, k_ret, k_text must be 4-d with a leading question dimension")
+        nq, n_new = q.shape[0], q.shape[1]
+        n_ret, stride = k_ret.shape[1], k_text.shape[1]
+        if k_ret.shape[0] != nq or v_ret.shape != k_ret.shape:
+            raise ValueError("k_ret / v_ret must be [n_questions, n_ret, Hkv, D]")
+        if k_text.shape[0] != nq or v_text.shape != k_text.shape:
+            raise ValueError("k_text / v_text must be [n_questions, text_stride, Hkv, D]")
+        out = torch.empty_like(q) if out is None else out
+        if out.shape != q.shape:
+            raise ValueError("out must have the shape of q")
+        self._check(self._lib.rekv_decode_attention(
+            self._h, self._dev(q, last=qh, name="q"),
+            self._dev(k_ret, last=kh, name="k_ret") if n_ret else None,
+            self._dev(v_ret, last=kh, name="v_ret") if n_ret else None, n_ret,
+            self._dev(k_text, last=kh, name="k_text"), self._dev(v_text, last=kh, name="v_text"),
+            stride, n_text_tokens, nq, n_new, self._dev(out, last=qh, name="out"), _stream()))
         return out
 
     def offload_kv(self, dev_k, dev_v, host_k, host_v, first_frame: int, n_frames: int):

@@ -314,6 +314,72 @@ def test_qa_attention_matches_oracle(w, nq, n_ret_frames):
 
 
 # ----------------------------------------------------------------------------------------
+# answer decoding, Eq. 3 with X = the tokens being decoded
+# ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("w,nq,n_ret_frames,n_gen,n_new,slack", [
+    (W.C1, 1, 16, 20, 1, 12), (W.C1, 3, 5, 9, 4, 0), (W.C1, 2, 0, 0, 1, 3),
+    (W.C4.scaled(n_q_tokens=17), 5, 3, 30, 1, 1), (W.C2, 1, 64, 128, 1, 0), (W.C1, 1, 16, 70, 40, 5),
+    (W.C0.scaled(tokens_per_frame=7, name="C0d"), 2, 3, 6, 2, 2)],
+    ids=["7B-k16", "7B-3q-4new", "no-retrieved", "72B-5q", "hour-k64-128gen", "7B-40new", "f32"])
+def test_decode_attention_matches_oracle(w, nq, n_ret_frames, n_gen, n_new, slack):
+    """Text KV = the question's tokens followed by n_gen generated ones; the last n_new are
+    decoded.  Rows of the text buffers past the valid ones hold NaN: reading them would
+    show in the output."""
+    w = w.scaled(n_frames=max(2 * n_ret_frames, 4))
+    r = Rekv.for_workload(w)
+    k, v = W.frames_k(w, 0, w.n_frames), W.frames_v(w, 0, w.n_frames)
+    nf = w.tokens_per_frame
+    n_text = w.n_q_tokens + n_gen
+    stride = n_text + slack
+    assert n_gen <= w.n_q_tokens * 4
+    qs, kts, vts, rks, rvs = [], [], [], [], []
+    for i in range(nq):
+        parts = [W.question_qkv(w, i + 64 * j) for j in range(1 + (n_gen + w.n_q_tokens - 1) // w.n_q_tokens)]
+        qt, kt, vt = (np.concatenate([p[c] for p in parts])[:n_text] for c in range(3))
+        frames = list(range(i % 2, i % 2 + n_ret_frames))
+        rk, rv = O.gather_kv(k, v, frames, nf)
+        qs.append(qt[n_text - n_new:]); kts.append(kt); vts.append(vt); rks.append(rk); rvs.append(rv)
+    pad = np.full((nq, slack, w.n_kv_heads, w.head_dim), np.nan)
+    shape_ret = (nq, n_ret_frames * nf, w.n_kv_heads, w.head_dim)
+    out = r.decode_attention(dev(np.stack(qs), w), dev(np.stack(rks).reshape(shape_ret), w),
+                             dev(np.stack(rvs).reshape(shape_ret), w),
+                             dev(np.concatenate([np.stack(kts), pad], axis=1), w),
+                             dev(np.concatenate([np.stack(vts), pad], axis=1), w), n_text)
+    out = host(out)
+    assert np.isfinite(out).all()
+    for i in range(nq):
+        ref = O.decode_attention(qs[i], rks[i], rvs[i], kts[i], vts[i])
+        err = np.abs(out[i] - ref).max()
+        assert err < TOL[w.dtype], (i, err)
+
+
+def test_decode_attention_rejects_bad_arguments():
+    w = W.C1
+    r = Rekv.for_workload(w)
+    q = torch.zeros((1, 2, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=DEV)
+    kr = torch.zeros((1, 8, w.n_kv_heads, w.head_dim), dtype=torch.bfloat16, device=DEV)
+    kt = torch.zeros((1, 4, w.n_kv_heads, w.head_dim), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(RekvError):
+        r.decode_attention(q, kr, kr, kt, kt, 1)       # fewer text rows than new tokens
+    with pytest.raises(RekvError):
+        r.decode_attention(q, kr, kr, kt, kt, 5)       # more valid rows than the buffer holds
+
+
+def test_probes_copy_is_exact_and_mfma_reports_its_work():
+    r = Rekv.for_workload(W.C1)
+    src = torch.randint(0, 255, (3 * 1024 * 1024 + 48,), dtype=torch.uint8, device=DEV)
+    dst = torch.zeros_like(src)
+    assert r.probe_copy(dst, src) == src.numel()
+    assert torch.equal(dst, src)
+    sink = torch.empty(8 * 256, dtype=torch.float32, device=DEV)
+    flop = r.probe_mfma(sink, 8, 10)
+    assert flop == 2.0 * 32 * 32 * 16 * 4 * 4 * 8 * 10
+    assert torch.isfinite(sink).all()
+    with pytest.raises(RekvError):
+        r.probe_copy(dst[:40], src[:40])                # not a multiple of 16 bytes
+
+
+# ----------------------------------------------------------------------------------------
 # the benchmark's launch configuration at full size, on sampled chunks
 # ----------------------------------------------------------------------------------------
 def test_c1_full_size_sampled_chunks_and_retrieval():
