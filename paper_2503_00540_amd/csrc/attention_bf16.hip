@@ -162,6 +162,9 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     const int row = m0 + wave * WM + col;        // this lane's query row
     const int tok = row / G;                      // its token inside the item
     const bool row_ok = row < m_rows;
+    // A wavefront whose 32 rows all lie past the last query row (a decode step has only G rows)
+    // keeps fetching tiles and joining the barriers but computes nothing.
+    const bool wave_active = ENCODE || m0 + wave * WM < m_rows;
 
     // tile list: tiles_a tiles of segment A (the first a_full of them whole and unmasked), then
     // the causal tiles of segment B this row block can see
@@ -291,6 +294,10 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
             dma_any(ka, kb, t + 4, KL);
             dma_any(va, vb, t + 3, STAGES * TILE_B + VL);
         }
+        if (!wave_active) {
+            step_barrier<2 * DMA_PER_STEP>();
+            return;
+        }
         // All LDS operand reads of this step are issued first; the running-maximum work below
         // covers their latency, and the MFMAs then issue back to back.
         bf16x8 kf[D / 16];
@@ -387,7 +394,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
         dma_any(va, vb, t_begin + 1, VB + TILE_B);
         dma_any(va, vb, t_begin + 2, VB + 2 * TILE_B);
         step_barrier<0>();
-        {
+        if (wave_active) {
             bf16x8 kf0[D / 16];
             load_k(0, kf0);
             qk(kf0, s_a);
@@ -446,56 +453,86 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
         const int64_t rows_pad = (int64_t)a.m_tiles * BM;
         const int64_t base = (((int64_t)item * p.n_kv_heads + kvh) * a.n_splits + split) * rows_pad + row;
         float* po = a.part_o + base * D;
+        if (row_ok) {                  // the merge reads only real rows
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db)
+            for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-            for (int j4 = 0; j4 < 4; ++j4) {
-                f32x4 w = {o[db][j4 * 4], o[db][j4 * 4 + 1], o[db][j4 * 4 + 2], o[db][j4 * 4 + 3]};
-                *reinterpret_cast<f32x4*>(po + db * 32 + j4 * 8 + hh * 4) = w;
-            }
-        if (hh == 0) {
+                for (int j4 = 0; j4 < 4; ++j4) {
+                    f32x4 w = {o[db][j4 * 4], o[db][j4 * 4 + 1], o[db][j4 * 4 + 2], o[db][j4 * 4 + 3]};
+                    *reinterpret_cast<f32x4*>(po + db * 32 + j4 * 8 + hh * 4) = w;
+                }
+        }
+        if (hh == 0 && row_ok) {
             f32x2 ml = {m_ref, l_tot};
             *reinterpret_cast<f32x2*>(a.part_ml + base * 2) = ml;
         }
     }
 }
 
-// Combines the split-KV partial results of one query row: the usual log-sum-exp merge.
+// Combines the split-KV partial results of one query row (the usual log-sum-exp merge).  One
+// workgroup per row: the splits are spread over 256 / (D/4) thread groups, each thread owning
+// four output dimensions, and the groups' sums meet in LDS.
 template <int D>
 __global__ __launch_bounds__(256) void attn_merge_kernel(KernelArgs a) {
     const AttnProblem& p = a.p;
     constexpr int TPR = D / 4;                 // threads per row
+    constexpr int NG = 256 / TPR;              // split groups
+    __shared__ float red_m[NG];
+    __shared__ float red_l[NG];
+    __shared__ f32x4 red_o[NG][TPR];
     const int G = p.n_q_heads / p.n_kv_heads;
     const int m_rows = p.len_q * G;
     const int64_t rows_pad = (int64_t)a.m_tiles * BM;
-    const int r_in_block = threadIdx.x / TPR, dq = threadIdx.x % TPR;
-    const int64_t gr = (int64_t)blockIdx.x * (256 / TPR) + r_in_block;   // over (item, kvh, row)
-    const int64_t ik = gr / m_rows;
-    const int row = (int)(gr % m_rows);
-    if (ik >= (int64_t)p.n_items * p.n_kv_heads) return;
+    const int64_t ik = blockIdx.x / m_rows;    // (item, KV head)
+    const int row = (int)(blockIdx.x % m_rows);
     const int item = (int)(ik / p.n_kv_heads), kvh = (int)(ik % p.n_kv_heads);
-    float m_all = -INFINITY;
-    for (int s = 0; s < a.n_splits; ++s)
-        m_all = fmaxf(m_all, a.part_ml[((ik * a.n_splits + s) * rows_pad + row) * 2]);
+    const int64_t base0 = ik * a.n_splits * rows_pad + row;
+    const int tid = threadIdx.x;
+
+    // each group folds its splits into one (m, l, O) triple; all loads of a group are
+    // independent, so the kernel pays one memory round trip when n_splits <= NG
+    const int g = tid / TPR, dq = tid % TPR;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    float l_all = 0.f;
-    for (int s = 0; s < a.n_splits; ++s) {
-        const int64_t base = (ik * a.n_splits + s) * rows_pad + row;
-        const float ms = a.part_ml[base * 2], ls = a.part_ml[base * 2 + 1];
-        const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - m_all);
-        l_all += w * ls;
+    float m = -INFINITY, l = 0.f;
+    for (int s = g; s < a.n_splits; s += NG) {
+        const int64_t base = base0 + s * rows_pad;
+        const f32x2 ml = *reinterpret_cast<const f32x2*>(a.part_ml + base * 2);
         const f32x4 v = *reinterpret_cast<const f32x4*>(a.part_o + base * D + dq * 4);
-        acc += v * w;
+        const float m_new = fmaxf(m, ml[0]);
+        const float w_old = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - m_new);
+        const float w_new = (ml[0] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[0] - m_new);
+        l = l * w_old + ml[1] * w_new;
+        acc = acc * w_old + v * w_new;
+        m = m_new;
     }
-    const float inv = 1.f / l_all;
-    const int tok = row / G;
-    bf16_t* orow = static_cast<bf16_t*>(p.out) +
-        (((int64_t)item * p.len_q + tok) * p.n_q_heads + kvh * G + (row - tok * G)) * D + dq * 4;
-    f32x2 lo = {acc[0] * inv, acc[1] * inv}, hi = {acc[2] * inv, acc[3] * inv};
-    u32x2 w;
-    w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
-    w.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
-    *reinterpret_cast<u32x2*>(orow) = w;
+    red_o[g][dq] = acc;
+    if (dq == 0) {
+        red_m[g] = m;
+        red_l[g] = l;
+    }
+    __syncthreads();
+    if (tid < TPR) {
+        float m_all = red_m[0];
+#pragma unroll
+        for (int i = 1; i < NG; ++i) m_all = fmaxf(m_all, red_m[i]);
+        f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+        float l_all = 0.f;
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+            const float w = (red_m[i] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(red_m[i] - m_all);
+            sum += red_o[i][tid] * w;
+            l_all += red_l[i] * w;
+        }
+        const float inv = 1.f / l_all;
+        const int tok = row / G;
+        bf16_t* orow = static_cast<bf16_t*>(p.out) +
+            (((int64_t)item * p.len_q + tok) * p.n_q_heads + kvh * G + (row - tok * G)) * D + tid * 4;
+        f32x2 lo = {sum[0] * inv, sum[1] * inv}, hi = {sum[2] * inv, sum[3] * inv};
+        u32x2 w;
+        w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+        w.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+        *reinterpret_cast<u32x2*>(orow) = w;
+    }
 }
 
 template <int D>
@@ -520,9 +557,7 @@ hipError_t launch(const AttnProblem& p, const AttnPlan& plan, void* workspace, h
     if (e != hipSuccess) return e;
     if (plan.n_splits > 1) {
         const int64_t rows = ik * p.len_q * (p.n_q_heads / p.n_kv_heads);
-        const int rpb = 256 / (D / 4);
-        hipLaunchKernelGGL(attn_merge_kernel<D>, dim3((unsigned)((rows + rpb - 1) / rpb)), dim3(256),
-                           0, stream, a);
+        hipLaunchKernelGGL(attn_merge_kernel<D>, dim3((unsigned)rows), dim3(256), 0, stream, a);
         e = hipGetLastError();
     }
     return e;
@@ -542,7 +577,10 @@ AttnPlan attn_bf16_plan(const AttnProblem& p) {
     const int64_t target = 512;              // about two workgroups per CU
     if (base < target) {
         splits = (int)((target + base - 1) / base);
-        const int cap = n_tiles / 8 > 1 ? n_tiles / 8 : 1;   // at least 8 tiles (256 keys) per split
+        // at least 8 tiles (256 keys) per split; 2 when only one wavefront per workgroup has rows
+        // (a decode step), where latency rather than the pipeline's fill cost decides
+        const int min_tiles = p.len_q * G <= WM ? 2 : 8;
+        const int cap = n_tiles / min_tiles > 1 ? n_tiles / min_tiles : 1;
         if (splits > cap) splits = cap;
     }
     plan.n_splits = splits;
