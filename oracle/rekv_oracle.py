@@ -201,6 +201,34 @@ def retrieve(frame_vecs, q_question, n_kv_heads, k, n_visible=None):
     return topk_frames(s, k), s
 
 
+def block_vectors(frame_vecs, b):
+    """Block-level retrieval: b consecutive frames form a block whose vector is the
+    average of their frame vectors.  The paper does not say what happens when b does
+    not divide the number of frames; here the last block holds the remaining frames and
+    averages over those.  frame_vecs [F, D'] -> [ceil(F / b), D']."""
+    fv = _f64(frame_vecs)
+    n_blocks = -(-fv.shape[0] // b)
+    return np.stack([fv[j * b:(j + 1) * b].mean(axis=0) for j in range(n_blocks)])
+
+
+def expand_blocks(blocks, b, n_frames):
+    """The frames of the given blocks, in the order of the blocks: block j holds frames
+    j*b .. min((j+1)*b, n_frames) - 1."""
+    return np.array([f for j in blocks for f in range(int(j) * b, min((int(j) + 1) * b, n_frames))],
+                    dtype=np.int64)
+
+
+def retrieve_blocks(frame_vecs, q_question, n_kv_heads, r, b):
+    """Block-level internal retrieval: Eq. 2 between the pooled question vector and the
+    block vectors, the ceil(r / b) most similar blocks (ties to the lower index, reported
+    ascending), and all of their frames as the retrieved set (so up to ceil(r/b)*b >= r
+    frames).  Returns (frame indices ascending, block indices ascending, block scores)."""
+    bv = block_vectors(frame_vecs, b)
+    s = cosine_scores(bv, question_vector(q_question, n_kv_heads))
+    blocks = topk_frames(s, -(-r // b))
+    return expand_blocks(blocks, b, np.asarray(frame_vecs).shape[0]), blocks, s
+
+
 def kv_cache_bytes(n_layers, n_frames, tokens_per_frame, n_kv_heads, head_dim,
                    bytes_per_value=2):
     """KV-cache size formula of the appendix: keys and values, every layer, every

@@ -306,6 +306,55 @@ def test_topk_against_exhaustive_sort():
     np.testing.assert_array_equal(O.topk_frames([0.1, 0.9, 0.9, 0.5], 3), [1, 2, 3])
 
 
+def test_block_retrieval():
+    F, nf, Hkv, D, Hq = 22, 3, 2, 4, 4
+    k = _rand((F * nf, Hkv, D), 41)
+    fv = O.frame_keys(k, F, nf)
+    qq = _rand((5, Hq, D), 42)
+    # b = 1 is frame-level retrieval
+    fr, bl, sc = O.retrieve_blocks(fv, qq, Hkv, 6, 1)
+    ref, ref_s = O.retrieve(fv, qq, Hkv, 6)
+    np.testing.assert_array_equal(fr, ref)
+    np.testing.assert_array_equal(bl, ref)
+    np.testing.assert_allclose(sc, ref_s, atol=1e-15)
+    # equal-sized blocks: the mean of b frame vectors is the mean of the block's b * N_f keys
+    bv = O.block_vectors(fv[:20], 4)
+    np.testing.assert_allclose(bv, O.frame_keys(k[:20 * nf], 5, 4 * nf), atol=1e-13)
+    # ragged tail, by hand: 22 frames in blocks of 4 -> 6 blocks, the last over frames 20, 21
+    bv = O.block_vectors(fv, 4)
+    assert bv.shape == (6, Hkv * D)
+    np.testing.assert_allclose(bv[5], (fv[20] + fv[21]) / 2, atol=1e-15)
+    np.testing.assert_allclose(bv[2], (fv[8] + fv[9] + fv[10] + fv[11]) / 4, atol=1e-15)
+    # ceil(r / b) blocks, whole blocks kept, frames ascending, the short last block kept short
+    fr, bl, sc = O.retrieve_blocks(fv, qq, Hkv, 10, 4)
+    assert len(bl) == 3 and (np.diff(bl) > 0).all() and sc.shape == (6,)
+    np.testing.assert_array_equal(bl, O.topk_frames(sc, 3))
+    want = [f for j in bl for f in range(4 * j, min(4 * j + 4, F))]
+    np.testing.assert_array_equal(fr, want)
+    np.testing.assert_array_equal(O.expand_blocks([1, 5], 4, F), [4, 5, 6, 7, 20, 21])
+    # more blocks asked for than exist: every frame, once
+    fr, bl, _ = O.retrieve_blocks(fv, qq, Hkv, 64, 4)
+    np.testing.assert_array_equal(fr, np.arange(F))
+    np.testing.assert_array_equal(bl, np.arange(6))
+
+
+def test_block_whose_frames_match_the_question_ranks_first():
+    """A block whose frame vectors all point along the question vector wins over blocks of
+    random frames, and wins even when only its mean, not each member, is aligned."""
+    rng = np.random.default_rng(43)
+    F, Dp, b = 24, 16, 4
+    fv = rng.standard_normal((F, Dp))
+    qv = rng.standard_normal(Dp)
+    q_tokens = np.tile(qv.reshape(1, 2, 8), (3, 1, 1))          # Hq = Hkv = 2: question vector = qv
+    spread = rng.standard_normal((b, Dp))
+    spread -= spread.mean(axis=0)                                # sums to zero over the block
+    fv[8:12] = 3.0 * qv + 2.0 * spread
+    fr, bl, sc = O.retrieve_blocks(fv, q_tokens, 2, 4, b)
+    np.testing.assert_array_equal(bl, [2])
+    np.testing.assert_array_equal(fr, [8, 9, 10, 11])
+    assert abs(sc[2] - 1.0) < 1e-12
+
+
 def test_gather():
     F, Nf, Hkv, D = 9, 4, 2, 3
     k, v = _rand((F * Nf, Hkv, D), 41), _rand((F * Nf, Hkv, D), 42)
