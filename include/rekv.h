@@ -125,6 +125,31 @@ rekv_status rekv_retrieve_topk(rekv_ctx* ctx, const float* frame_keys, int64_t f
                                float* scores, void* stream);
 
 /*
+ * Block-level retrieval (retrieval section and the block-size ablation): b consecutive
+ * frames form a block whose vector is the average of their frame vectors; blocks are scored
+ * and selected like frames, ceil(r / b) of them, and all their frames are retrieved.
+ * The paper leaves the case b not dividing the frame count open; here the last block holds
+ * the remaining frames.
+ *
+ * rekv_block_keys: block_keys[j] = mean of frame_keys[j*b .. min((j+1)*b, n_frames) - 1].
+ *   frame_keys  [n_frames, D'] fp32, 16-byte aligned;  block_keys  [ceil(n_frames / b), D'] fp32
+ *   A caller that scores blocks keeps this table up to date as frames arrive (re-running the
+ *   call on the last, still growing block) and passes it to rekv_retrieve_topk with
+ *   n_frames = the number of blocks and k = ceil(r / b).
+ * rekv_expand_blocks: turns the selected blocks into the frame list rekv_gather_kv takes.
+ *   block_idx   [n_questions, k_blocks] int32, ascending, -1 padded (rekv_retrieve_topk's idx)
+ *   frame_idx   [n_questions, k_blocks * b] int32: the blocks' frames in order; slots past the
+ *               end of the stream (the short last block) or of the selection hold -1, always
+ *               at the tail
+ *   n_sel       [n_questions] int32: frames listed per question; may be NULL
+ */
+rekv_status rekv_block_keys(rekv_ctx* ctx, const float* frame_keys, int32_t n_frames, int32_t b,
+                            float* block_keys, void* stream);
+rekv_status rekv_expand_blocks(rekv_ctx* ctx, const int32_t* block_idx, int32_t n_questions,
+                               int32_t k_blocks, int32_t b, int32_t n_frames, int32_t* frame_idx,
+                               int32_t* n_sel, void* stream);
+
+/*
  * Reload of the retrieved KV: copies the selected frames' key and value blocks into one
  * dense buffer per question, in the order idx gives them (ascending frame index).
  *

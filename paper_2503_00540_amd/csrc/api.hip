@@ -256,6 +256,29 @@ rekv_status rekv_retrieve_topk(rekv_ctx* c, const float* frame_keys, int64_t fra
     return e == hipSuccess ? REKV_OK : fail_hip(c, "retrieval launch", e);
 }
 
+rekv_status rekv_block_keys(rekv_ctx* c, const float* frame_keys, int32_t n_frames, int32_t b,
+                            float* block_keys, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!frame_keys || !block_keys) return fail(c, REKV_ERR_INVALID_ARG, "rekv_block_keys: null pointer");
+    if (!aligned16(frame_keys)) return fail(c, REKV_ERR_INVALID_ARG, "rekv_block_keys: frame_keys must be 16-byte aligned");
+    if (n_frames <= 0 || b <= 0) return fail(c, REKV_ERR_INVALID_ARG, "rekv_block_keys: n_frames=%d b=%d", n_frames, b);
+    const int d_prime = c->shape.n_kv_heads * c->shape.head_dim;
+    hipError_t e = rekv::block_keys_launch(frame_keys, n_frames, b, d_prime, block_keys, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "block_keys launch", e);
+}
+
+rekv_status rekv_expand_blocks(rekv_ctx* c, const int32_t* block_idx, int32_t n_questions, int32_t k_blocks,
+                               int32_t b, int32_t n_frames, int32_t* frame_idx, int32_t* n_sel, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!block_idx || !frame_idx) return fail(c, REKV_ERR_INVALID_ARG, "rekv_expand_blocks: null pointer");
+    if (n_questions <= 0 || k_blocks <= 0 || b <= 0 || n_frames <= 0 || (int64_t)k_blocks * b > (1 << 20))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_expand_blocks: n_questions=%d k_blocks=%d b=%d n_frames=%d (k_blocks*b <= 2^20)",
+                    n_questions, k_blocks, b, n_frames);
+    hipError_t e = rekv::expand_blocks_launch(block_idx, n_questions, k_blocks, b, n_frames, frame_idx, n_sel,
+                                              static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "expand_blocks launch", e);
+}
+
 rekv_status rekv_gather_kv(rekv_ctx* c, const void* src_k, const void* src_v, int32_t src_on_host,
                            int32_t n_src_frames, const int32_t* idx, int32_t n_questions, int32_t k,
                            void* dst_k, void* dst_v, void* stream_) {

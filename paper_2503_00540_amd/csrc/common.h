@@ -86,6 +86,11 @@ struct RetrieveArgs {
 };
 hipError_t retrieve_launch(const RetrieveArgs& a, hipStream_t stream);
 
+hipError_t block_keys_launch(const float* frame_keys, int n_frames, int b, int d_prime, float* block_keys,
+                             hipStream_t stream);
+hipError_t expand_blocks_launch(const int32_t* block_idx, int n_questions, int k_blocks, int b, int n_frames,
+                                int32_t* frame_idx, int32_t* n_sel, hipStream_t stream);
+
 hipError_t gather_launch(const void* src_k, const void* src_v, int n_src_frames, const int32_t* idx,
                          int n_blocks, size_t frame_bytes, void* dst_k, void* dst_v,
                          hipStream_t stream);

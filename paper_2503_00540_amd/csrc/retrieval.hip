@@ -321,6 +321,58 @@ hipError_t frame_keys_launch(const void* k, int n_frames, int tokens_per_frame, 
     return hipGetLastError();
 }
 
+namespace {
+
+// Frames of the selected blocks, in block order.  One workgroup per question; slot j*b + t of
+// the output is frame block[j]*b + t, or -1 past the end of the stream or of the selection.
+// Because blocks come in ascending order, only the last selected block can be the stream's
+// short one, so the -1 slots are always at the tail.
+__global__ __launch_bounds__(256) void expand_blocks_kernel(const int32_t* __restrict__ block_idx,
+                                                            int k_blocks, int b, int n_frames,
+                                                            int32_t* __restrict__ frame_idx,
+                                                            int32_t* __restrict__ n_sel) {
+    __shared__ int count;
+    const int q = blockIdx.x;
+    if (threadIdx.x == 0) count = 0;
+    __syncthreads();
+    const int n_slots = k_blocks * b;
+    int mine = 0;
+    for (int s = threadIdx.x; s < n_slots; s += 256) {
+        const int blk = block_idx[(int64_t)q * k_blocks + s / b];
+        const int64_t f = (int64_t)blk * b + s % b;
+        const bool ok = blk >= 0 && f < n_frames;
+        frame_idx[(int64_t)q * n_slots + s] = ok ? (int32_t)f : -1;
+        mine += ok;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mine += __shfl_xor(mine, off);
+    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(&count, mine);
+    __syncthreads();
+    if (threadIdx.x == 0 && n_sel) n_sel[q] = count;
+}
+
+}  // namespace
+
+hipError_t block_keys_launch(const float* frame_keys, int n_frames, int b, int d_prime, float* block_keys,
+                             hipStream_t stream) {
+    // a block vector is the mean of b rows of the fp32 frame table: the frame-vector kernel
+    // with b "tokens" per "frame"; the stream's short last block gets a launch of its own
+    const int n_full = n_frames / b, rest = n_frames % b;
+    hipError_t e = hipSuccess;
+    if (n_full > 0) e = frame_keys_launch(frame_keys, n_full, b, d_prime, REKV_F32, block_keys, stream);
+    if (e == hipSuccess && rest > 0)
+        e = frame_keys_launch(frame_keys + (int64_t)n_full * b * d_prime, 1, rest, d_prime, REKV_F32,
+                              block_keys + (int64_t)n_full * d_prime, stream);
+    return e;
+}
+
+hipError_t expand_blocks_launch(const int32_t* block_idx, int n_questions, int k_blocks, int b, int n_frames,
+                                int32_t* frame_idx, int32_t* n_sel, hipStream_t stream) {
+    hipLaunchKernelGGL(expand_blocks_kernel, dim3((unsigned)n_questions), dim3(256), 0, stream, block_idx,
+                       k_blocks, b, n_frames, frame_idx, n_sel);
+    return hipGetLastError();
+}
+
 hipError_t retrieve_launch(const RetrieveArgs& a, hipStream_t stream) {
     const int d_prime = a.n_kv_heads * a.head_dim;
     // token mean per query head: [n_questions, Hq * D] fp32, then the group mean: [n_questions, D']

@@ -23,7 +23,7 @@ _DTYPES = {"f32": (REKV_F32, torch.float32), "bf16": (REKV_BF16, torch.bfloat16)
 # Every entry point include/rekv.h declares.
 SYMBOLS = ("rekv_create", "rekv_destroy", "rekv_last_error", "rekv_encode_chunk",
            "rekv_frame_keys", "rekv_retrieve_topk", "rekv_gather_kv", "rekv_qa_attention",
-           "rekv_decode_attention",
+           "rekv_decode_attention", "rekv_block_keys", "rekv_expand_blocks",
            "rekv_offload_kv", "rekv_offload_wait", "rekv_probe_copy", "rekv_probe_mfma")
 
 
@@ -65,6 +65,9 @@ def lib() -> ctypes.CDLL:
                                  c_int32, c_void_p, c_void_p, c_void_p]
     L.rekv_qa_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p,
                                     c_int32, c_int32, c_void_p, c_void_p]
+    L.rekv_block_keys.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p]
+    L.rekv_expand_blocks.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_void_p,
+                                     c_void_p, c_void_p]
     L.rekv_decode_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p,
                                         c_int64, c_int32, c_int32, c_int32, c_void_p, c_void_p]
     L.rekv_offload_kv.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32,
@@ -185,6 +188,32 @@ class Rekv:
             self._dev(q_question, last=(self.n_q_heads, self.head_dim), name="q_question"), nq, n_q_tokens, k,
             idx.data_ptr(), n_sel.data_ptr(), scores.data_ptr() if want_scores else None, _stream()))
         return idx, n_sel, scores
+
+    def block_keys(self, frame_keys, n_frames: int, b: int, out=None):
+        """frame_keys [>= n_frames, D'] fp32 -> block vectors [ceil(n_frames / b), D'] fp32."""
+        d_prime = self.n_kv_heads * self.head_dim
+        n_blocks = -(-n_frames // b) if b > 0 else 0
+        if frame_keys.numel() < n_frames * d_prime:
+            raise ValueError("frame_keys holds fewer than n_frames rows")
+        out = torch.empty((max(n_blocks, 1), d_prime), dtype=torch.float32, device=frame_keys.device) \
+            if out is None else out
+        if out.numel() < n_blocks * d_prime:
+            raise ValueError("out holds fewer than ceil(n_frames / b) rows")
+        self._check(self._lib.rekv_block_keys(self._h, self._dev(frame_keys, torch.float32, name="frame_keys"),
+                                              n_frames, b, self._dev(out, torch.float32, name="block_keys"),
+                                              _stream()))
+        return out
+
+    def expand_blocks(self, block_idx, b: int, n_frames: int):
+        """block_idx [n_questions, k_blocks] int32 -> (frame_idx [n_questions, k_blocks * b], n_sel)."""
+        if block_idx.dim() != 2 or block_idx.dtype != torch.int32 or not block_idx.is_cuda:
+            raise ValueError("block_idx must be a device tensor [n_questions, k_blocks] int32")
+        nq, kb = block_idx.shape
+        frame_idx = torch.empty((nq, kb * max(b, 0)), dtype=torch.int32, device=block_idx.device)
+        n_sel = torch.empty((nq,), dtype=torch.int32, device=block_idx.device)
+        self._check(self._lib.rekv_expand_blocks(self._h, block_idx.contiguous().data_ptr(), nq, kb, b, n_frames,
+                                                 frame_idx.data_ptr(), n_sel.data_ptr(), _stream()))
+        return frame_idx, n_sel
 
     def gather_kv(self, src_k, src_v, idx, n_src_frames: int | None = None, dst_k=None, dst_v=None,
                   host_mode: int = 2):

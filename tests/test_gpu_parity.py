@@ -199,6 +199,94 @@ def test_retrieval_matches_oracle(w, nq):
         assert int(n_sel[i]) == w.top_k
 
 
+# ----------------------------------------------------------------------------------------
+# block-level retrieval
+# ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("b", [1, 2, 4, 8, 16])
+def test_block_retrieval_hour_long_table(b):
+    """The block-size ablation's setting (r = 64, b in 1..16) on a table as long as the
+    hour-long stream's: 3,600 frame vectors of 512 dims, drawn directly (the frame-vector
+    step has its own test), with a run of frames near each question so that something stands
+    out.  3,600 is not a multiple of 16 or 32: b = 16 has a full last block, see the ragged
+    case below for the short one."""
+    w = W.C2
+    F, dp, r_frames, nq = 3600, w.d_prime, 64, 3
+    rng = np.random.default_rng(1000 + b)
+    table = rng.standard_normal((F, dp)).astype(np.float32)
+    qs = []
+    for i in range(nq):
+        q = rng.standard_normal((w.n_q_tokens, w.n_q_heads, w.head_dim))
+        qv = O.question_vector(q, w.n_kv_heads)
+        lo = 200 + 1000 * i
+        table[lo:lo + 24] += (8.0 * qv).astype(np.float32)
+        qs.append(W.round_to_bf16(q))
+    r = Rekv.for_workload(w)
+    t_dev = torch.from_numpy(table).to(DEV)
+    bk = r.block_keys(t_dev, F, b)
+    bk_ref = O.block_vectors(table, b)
+    assert bk.shape[0] == bk_ref.shape[0] == -(-F // b)
+    assert np.abs(host(bk) - bk_ref).max() < 1e-5
+    kb = -(-r_frames // b)
+    blk, n_blk, scores = r.retrieve_topk(bk, bk.shape[0], dev(np.stack(qs), w), kb, want_scores=True)
+    fidx, n_sel = r.expand_blocks(blk, b, F)
+    assert fidx.shape == (nq, kb * b)
+    for i in range(nq):
+        ref_frames, ref_blocks, ref_s = O.retrieve_blocks(table, qs[i], w.n_kv_heads, r_frames, b)
+        assert np.abs(host(scores)[i] - ref_s).max() < 1e-5
+        check_topk(blk[i].cpu().numpy(), ref_s, kb)
+        got_blocks = blk[i].cpu().numpy()
+        np.testing.assert_array_equal(fidx[i].cpu().numpy(), O.expand_blocks(got_blocks, b, F))
+        assert int(n_sel[i]) == kb * b and int(n_blk[i]) == kb
+        lo = 200 + 1000 * i                      # the planted run's fully covered blocks are in
+        inside = [j for j in range(F // b) if j * b >= lo and (j + 1) * b <= lo + 24]
+        assert set(inside) <= set(got_blocks.tolist())
+
+
+def test_block_retrieval_ragged_stream_end_to_end():
+    """Frames -> frame vectors -> block vectors -> block top-k -> frame list -> gather, on a
+    stream whose last block is short and is the one the question points at."""
+    b, r_frames = 8, 20
+    w = W.C1.scaled(n_frames=59, tokens_per_frame=12, n_q_tokens=9, name="C1-blocks")
+    k, v = W.frames_k(w, 0, w.n_frames), W.frames_v(w, 0, w.n_frames)
+    fk_ref = O.frame_keys(k, w.n_frames, w.tokens_per_frame)
+    # the question: near the mean key of the last three frames (the short block 7 = frames 56..58)
+    rng = np.random.default_rng(77)
+    target = fk_ref[56:59].mean(axis=0).reshape(w.n_kv_heads, w.head_dim)
+    q = np.repeat(target, w.group, axis=0)[None] + 0.3 * rng.standard_normal((w.n_q_tokens, w.n_q_heads, w.head_dim))
+    q = W.round_to_bf16(q)
+    r = Rekv.for_workload(w)
+    dk, dv = dev(k, w), dev(v, w)
+    fk = r.frame_keys(dk, w.n_frames)
+    bk = r.block_keys(fk, w.n_frames, b)
+    bk_ref = O.block_vectors(fk_ref, b)
+    assert bk.shape[0] == 8 and np.abs(host(bk) - bk_ref).max() < 1e-5
+    kb = -(-r_frames // b)                                                    # 3 blocks
+    blk, _, scores = r.retrieve_topk(bk, 8, dev(q[None], w), kb, want_scores=True)
+    ref_frames, ref_blocks, ref_s = O.retrieve_blocks(fk_ref, q, w.n_kv_heads, r_frames, b)
+    assert np.abs(host(scores)[0] - ref_s).max() < 1e-5
+    check_topk(blk[0].cpu().numpy(), ref_s, kb)
+    assert 7 in blk[0].tolist() and 7 in ref_blocks.tolist()
+    fidx, n_sel = r.expand_blocks(blk, b, w.n_frames)
+    got = fidx[0].cpu().numpy()
+    n = int(n_sel[0])
+    assert n == 2 * b + 3 and (got[n:] == -1).all()
+    np.testing.assert_array_equal(got[:n], O.expand_blocks(blk[0].cpu().numpy(), b, w.n_frames))
+    gk, gv = r.gather_kv(dk, dv, fidx, n_src_frames=w.n_frames)
+    rk, rv = O.gather_kv(k, v, got[:n], w.tokens_per_frame)
+    nt = n * w.tokens_per_frame
+    np.testing.assert_array_equal(host(gk)[0, :nt], rk)
+    np.testing.assert_array_equal(host(gv)[0, :nt], rv)
+    assert not host(gk)[0, nt:].any() and not host(gv)[0, nt:].any()       # -1 slots are zero-filled
+    # more blocks asked for than the stream has: all frames, once, then -1
+    blk_all, n_blk, _ = r.retrieve_topk(bk, 8, dev(q[None], w), 11)
+    fidx, n_sel = r.expand_blocks(blk_all, b, w.n_frames)
+    assert int(n_blk[0]) == 8 and int(n_sel[0]) == w.n_frames
+    np.testing.assert_array_equal(fidx[0, :w.n_frames].cpu().numpy(), np.arange(w.n_frames))
+    assert (fidx[0, w.n_frames:] == -1).all()
+    with pytest.raises(RekvError):
+        r.block_keys(fk, w.n_frames, 0)
+
+
 def test_per_layer_tables_retrieve_independently():
     """Each 'question' row has its own frame-key table (one per layer)."""
     w = W.C3.scaled(n_frames=40, n_layers=3)
