@@ -288,6 +288,38 @@ def main() -> None:
         torch.cuda.synchronize()
         streaming_s = time.perf_counter() - t1
 
+    # beyond the step: one decode-step attention over the retrieved KV (Eq. 3, X = the current
+    # token, 64 tokens already generated) and block-level retrieval at b = 8, timed on their own
+    def timed_us(fn, reps=20):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
+    n_text = w.n_q_tokens + 64
+    g = torch.Generator(device="cuda:0").manual_seed(7)
+    kt = torch.randn((nq, 256, w.n_kv_heads, w.head_dim), device="cuda:0", generator=g).to(tdt)
+    vt = torch.randn((nq, 256, w.n_kv_heads, w.head_dim), device="cuda:0", generator=g).to(tdt)
+    q1 = torch.randn((nq, 1, w.n_q_heads, w.head_dim), device="cuda:0", generator=g).to(tdt)
+    o1 = torch.empty_like(q1)
+    decode_us = timed_us(lambda: r.decode_attention(q1, gk[:nq], gv[:nq], kt, vt, n_text, out=o1))
+    decode_bytes = 2 * nq * (w.top_k * nf + n_text) * d_prime * (2 if w.dtype == "bf16" else 4)
+    b_blk = 8
+    kb = -(-w.top_k // b_blk)
+    bk = torch.empty((-(-F // b_blk), d_prime), dtype=torch.float32, device="cuda:0")
+    qq0 = d["qq"][:nq]
+
+    def block_retrieval():
+        r.block_keys(fk[0], F, b_blk, out=bk)
+        blk, _, _ = r.retrieve_topk(bk, bk.shape[0], qq0, kb)
+        return r.expand_blocks(blk, b_blk, F)
+    block_us = timed_us(block_retrieval)
+
     planted = [set(p) <= set(idx[i].tolist()) for i, p in enumerate(d["planted"])]
     fl = encode_flops(w)                                   # one launch = one layer's stream
     if w.dtype == "bf16":
@@ -326,6 +358,10 @@ def main() -> None:
                 "retrieve_table_GBs": L * F * d_prime * 4 / (ms["retrieve"] * 1e-3) / 1e9,
                 "qa_TFLOPs": L * qa_flops(w) / (ms["qa"] * 1e-3) / 1e12, "peak_GBs": PEAK_HBM_GBS},
         "planted_frames_retrieved": all(planted),
+        "decode_step": {"us": decode_us, "kv_GBs": decode_bytes / decode_us / 1e3,
+                        "what": f"{nq} question(s), 1 new token over {w.top_k * nf} retrieved + {n_text} text tokens, one layer"},
+        "block_retrieval": {"us": block_us, "b": b_blk, "blocks_selected": kb,
+                            "what": "block vectors from the frame table + scores + top-k + frame list, one layer"},
         "box_peaks": box_peaks(r, torch),
     }
     if not args.no_cpu_baseline:
