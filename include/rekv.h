@@ -226,7 +226,8 @@ rekv_status rekv_offload_wait(rekv_ctx* ctx);
  *   aligned, device memory, not overlapping).  Moves n_bytes in and n_bytes out of HBM; it
  *   is also the kernel of known size that the HBM byte counters are calibrated on.
  * rekv_probe_mfma: n_workgroups workgroups of 4 wavefronts, each wavefront issuing
- *   4 * n_iters independent-chain bf16 32x32x16 MFMAs from registers.  sink receives
+ *   4 * n_iters (n_iters rounded up to a multiple of 8) bf16 32x32x16 MFMAs on four independent
+ *   accumulators, cycling through 8 operand fragment pairs held in registers.  sink receives
  *   n_workgroups * 256 floats (so the work is not optimised away); *flop (host pointer, may
  *   be NULL) receives the floating-point operations of the launch.
  */

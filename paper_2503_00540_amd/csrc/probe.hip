@@ -36,24 +36,39 @@ __global__ __launch_bounds__(COPY_THREADS) void probe_copy_kernel(const u32x4* _
 constexpr int MFMA_THREADS = 256;
 constexpr int MFMA_CHAINS = 4;   // independent accumulators per wavefront
 
+constexpr int MFMA_FRAGS = 8;    // distinct A and B operand fragments cycled through
+
 __global__ __launch_bounds__(MFMA_THREADS) void probe_mfma_kernel(float* __restrict__ sink, int n_iters) {
-    // operands: pseudo-random sign and mantissa, magnitudes in [1, 2), so the data toggles the
-    // multiplier inputs the way real activations do while the sums stay finite
-    bf16x8 a, b;
+    // Operands: approximately N(0, 1) values (sum of four hashed bytes, centred and scaled), a
+    // different fragment pair for every MFMA of an unrolled group, so that signs, exponents and
+    // mantissas at the multiplier inputs toggle the way activations make them toggle.  The sustained
+    // clock, and with it the rate, depends on that: constant or small-integer operands run far
+    // faster than any real kernel can.  The sums are random walks and stay finite.
+    bf16x8 a[MFMA_FRAGS], b[MFMA_FRAGS];
+    auto normal_like = [](uint32_t h) {
+        const int sum = (int)(h & 255u) + (int)((h >> 8) & 255u) + (int)((h >> 16) & 255u) + (int)(h >> 24);
+        return (__bf16)((float)(sum - 510) * (1.f / 147.8f));
+    };
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const uint32_t h = (threadIdx.x * 8u + i + 1u) * 2654435761u;
-        a[i] = __builtin_bit_cast(__bf16, (uint16_t)(0x3f80u | ((h >> 9) & 0x7fu) | ((h >> 4) & 0x8000u)));
-        b[i] = __builtin_bit_cast(__bf16, (uint16_t)(0x3f80u | ((h >> 17) & 0x7fu) | ((h >> 12) & 0x8000u)));
-    }
+    for (int f = 0; f < MFMA_FRAGS; ++f)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t idx = (threadIdx.x * MFMA_FRAGS + f) * 8u + i + 1u;
+            a[f][i] = normal_like(idx * 2654435761u);
+            b[f][i] = normal_like((idx ^ 0x5bd1e995u) * 2246822519u);
+        }
     f32x16 acc[MFMA_CHAINS];
 #pragma unroll
     for (int c = 0; c < MFMA_CHAINS; ++c)
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[c][j] = 0.f;
-    for (int it = 0; it < n_iters; ++it) {
+    for (int it = 0; it < n_iters; it += MFMA_FRAGS) {
 #pragma unroll
-        for (int c = 0; c < MFMA_CHAINS; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
+        for (int u = 0; u < MFMA_FRAGS; ++u)
+#pragma unroll
+            for (int c = 0; c < MFMA_CHAINS; ++c)
+                acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(u + c) % MFMA_FRAGS], b[(u * 3 + c) % MFMA_FRAGS],
+                                                                 acc[c], 0, 0, 0);
     }
     float s = 0.f;
 #pragma unroll
@@ -81,6 +96,7 @@ hipError_t launch_probe_mfma(float* sink, int32_t n_workgroups, int32_t n_iters,
 }
 
 double probe_mfma_flop(int32_t n_workgroups, int32_t n_iters) {
+    n_iters = (n_iters + MFMA_FRAGS - 1) / MFMA_FRAGS * MFMA_FRAGS;   // the loop runs whole groups
     return 2.0 * 32 * 32 * 16 * MFMA_CHAINS * (MFMA_THREADS / 64) * (double)n_workgroups * (double)n_iters;
 }
 

@@ -460,8 +460,8 @@ def test_probes_copy_is_exact_and_mfma_reports_its_work():
     assert r.probe_copy(dst, src) == src.numel()
     assert torch.equal(dst, src)
     sink = torch.empty(8 * 256, dtype=torch.float32, device=DEV)
-    flop = r.probe_mfma(sink, 8, 10)
-    assert flop == 2.0 * 32 * 32 * 16 * 4 * 4 * 8 * 10
+    flop = r.probe_mfma(sink, 8, 16)
+    assert flop == 2.0 * 32 * 32 * 16 * 4 * 4 * 8 * 16
     assert torch.isfinite(sink).all()
     with pytest.raises(RekvError):
         r.probe_copy(dst[:40], src[:40])                # not a multiple of 16 bytes
