@@ -320,6 +320,15 @@ def main() -> None:
         return r.expand_blocks(blk, b_blk, F)
     block_us = timed_us(block_retrieval)
 
+    # the same encode launch on all-zero inputs: same instructions and traffic, least switching
+    # power; the gap to the timed figure is what the data's toggling costs in sustained clock
+    zero_tflops = None
+    if w.dtype == "bf16":
+        zq, zk = torch.zeros_like(d["q"][0]), torch.zeros_like(d["k"][0])
+        zero_us = timed_us(lambda: r.encode_chunk(zq, zk, zk, 0, w.l_x, n_chunks, w.l_l, out=out), reps=5)
+        zero_tflops = encode_flops(w) / zero_us / 1e6
+        del zq, zk
+
     planted = [set(p) <= set(idx[i].tolist()) for i, p in enumerate(d["planted"])]
     fl = encode_flops(w)                                   # one launch = one layer's stream
     if w.dtype == "bf16":
@@ -362,7 +371,7 @@ def main() -> None:
                         "what": f"{nq} question(s), 1 new token over {w.top_k * nf} retrieved + {n_text} text tokens, one layer"},
         "block_retrieval": {"us": block_us, "b": b_blk, "blocks_selected": kb,
                             "what": "block vectors from the frame table + scores + top-k + frame list, one layer"},
-        "box_peaks": box_peaks(r, torch),
+        "box_peaks": dict(box_peaks(r, torch), encode_on_zero_inputs_TFLOPs=zero_tflops),
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w)
