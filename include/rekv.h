@@ -125,6 +125,23 @@ rekv_status rekv_retrieve_topk(rekv_ctx* ctx, const float* frame_keys, int64_t f
                                float* scores, void* stream);
 
 /*
+ * External retrieval scoring (external video KV-cache retrieval, Eq. 2 with its temperature):
+ * the same cosine ranking on embeddings the caller computed elsewhere (the paper uses a
+ * CLIP-like encoder pair, which is not part of this library).
+ *   Sim(v, q) = v.q / (tau |v| |q|); a zero-norm vector scores 0; selection as in
+ *   rekv_retrieve_topk (ties to the lower index, ascending output, -1 padding).
+ *
+ *   frame_emb  [n_frames, dim] fp32, 16-byte aligned, dim a multiple of 4 (<= 12284), one
+ *              table shared by all questions
+ *   q_emb      [n_questions, dim] fp32, 16-byte aligned
+ *   tau        > 0 (a positive tau does not change the ranking, only the reported scores)
+ *   idx, n_sel, scores   as in rekv_retrieve_topk
+ */
+rekv_status rekv_retrieve_external(rekv_ctx* ctx, const float* frame_emb, int32_t n_frames, int32_t dim,
+                                   const float* q_emb, int32_t n_questions, float tau, int32_t k,
+                                   int32_t* idx, int32_t* n_sel, float* scores, void* stream);
+
+/*
  * Block-level retrieval (retrieval section and the block-size ablation): b consecutive
  * frames form a block whose vector is the average of their frame vectors; blocks are scored
  * and selected like frames, ceil(r / b) of them, and all their frames are retrieved.

@@ -201,6 +201,14 @@ def retrieve(frame_vecs, q_question, n_kv_heads, k, n_visible=None):
     return topk_frames(s, k), s
 
 
+def retrieve_external(frame_emb, q_emb, k, tau=1.0):
+    """External retrieval for one question: Eq. 2 with its temperature on embeddings that
+    a CLIP-like encoder pair produced elsewhere, then the same top-k rule.
+    frame_emb [F, D], q_emb [D].  Returns (indices ascending, scores [F])."""
+    s = cosine_scores(frame_emb, q_emb, tau)
+    return topk_frames(s, k), s
+
+
 def block_vectors(frame_vecs, b):
     """Block-level retrieval: b consecutive frames form a block whose vector is the
     average of their frame vectors.  The paper does not say what happens when b does

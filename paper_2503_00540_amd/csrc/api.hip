@@ -252,8 +252,38 @@ rekv_status rekv_retrieve_topk(rekv_ctx* c, const float* frame_keys, int64_t fra
     a.q_heads = static_cast<float*>(c->ws);
     a.q_vec = reinterpret_cast<float*>(static_cast<char*>(c->ws) + qh_bytes);
     a.scores = scores ? scores : reinterpret_cast<float*>(static_cast<char*>(c->ws) + qv_bytes);
+    a.q_vec_given = nullptr; a.dim = 0; a.inv_tau = 1.f;
     hipError_t e = rekv::retrieve_launch(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? REKV_OK : fail_hip(c, "retrieval launch", e);
+}
+
+rekv_status rekv_retrieve_external(rekv_ctx* c, const float* frame_emb, int32_t n_frames, int32_t dim,
+                                   const float* q_emb, int32_t n_questions, float tau, int32_t k,
+                                   int32_t* idx, int32_t* n_sel, float* scores, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!frame_emb || !q_emb || !idx) return fail(c, REKV_ERR_INVALID_ARG, "rekv_retrieve_external: null pointer");
+    if (!aligned16(frame_emb) || !aligned16(q_emb))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_retrieve_external: embeddings must be 16-byte aligned");
+    if (n_frames <= 0 || n_questions <= 0 || k <= 0 || k > 4096 || dim <= 0 || dim % 4 != 0 || !(tau > 0.f))
+        return fail(c, REKV_ERR_INVALID_ARG,
+                    "rekv_retrieve_external: n_frames=%d n_questions=%d k=%d (1..4096) dim=%d (multiple of 4) tau=%g (> 0)",
+                    n_frames, n_questions, k, dim, (double)tau);
+    if ((size_t)(dim + 1) * sizeof(float) > 48 * 1024)
+        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_retrieve_external: dim=%d exceeds 12284", dim);
+    if (n_questions > 65535) return fail(c, REKV_ERR_UNSUPPORTED, "rekv_retrieve_external: at most 65535 questions per call");
+    if (!scores) {
+        rekv_status s = reserve(c, (size_t)n_questions * n_frames * sizeof(float));
+        if (s != REKV_OK) return s;
+    }
+    rekv::RetrieveArgs a;
+    memset(&a, 0, sizeof(a));
+    a.frame_keys = frame_emb; a.frame_keys_stride = 0; a.n_frames = n_frames;
+    a.n_questions = n_questions; a.k = k;
+    a.idx = idx; a.n_sel = n_sel;
+    a.scores = scores ? scores : static_cast<float*>(c->ws);
+    a.q_vec_given = q_emb; a.dim = dim; a.inv_tau = 1.f / tau;
+    hipError_t e = rekv::retrieve_launch(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "external retrieval launch", e);
 }
 
 rekv_status rekv_block_keys(rekv_ctx* c, const float* frame_keys, int32_t n_frames, int32_t b,

@@ -83,6 +83,11 @@ struct RetrieveArgs {
     float* scores;   // [n_questions, n_frames], never NULL here (workspace if the caller gave none)
     float* q_heads;  // [n_questions, Hq * D] workspace: token means per query head
     float* q_vec;    // [n_questions, D'] workspace: pooled question vectors
+    // External retrieval (Eq. 2 on given embeddings): q_question == NULL, q_vec_given holds the
+    // question embeddings, dim their length; scores are divided by tau.
+    const float* q_vec_given;
+    int32_t dim;     // vector length; 0 = Hkv * D
+    float inv_tau;   // 1 for internal retrieval
 };
 hipError_t retrieve_launch(const RetrieveArgs& a, hipStream_t stream);
 

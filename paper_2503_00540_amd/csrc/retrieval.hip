@@ -129,7 +129,7 @@ __device__ inline float transpose_reduce(float (&v)[N], int lane) {
 template <int FR, int QBT>
 __global__ __launch_bounds__(SCORE_WAVES * 64) void score_kernel(
     const float* __restrict__ frame_keys, int64_t fk_stride, int n_frames, int d_prime,
-    const float* __restrict__ q_vec, int n_questions, float* __restrict__ scores) {
+    const float* __restrict__ q_vec, int n_questions, float inv_tau, float* __restrict__ scores) {
     static_assert(FR * QBT <= 64 && (FR & (FR - 1)) == 0 && (QBT & (QBT - 1)) == 0, "butterfly sizes");
     extern __shared__ float qs[];            // [QBT][d_prime] then [QBT] squared norms
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(SCORE_WAVES * 64) void score_kernel(
         const bool writer = (lane & ((1 << (6 - LOG_N)) - 1)) == 0;
         if (writer && f0 + fr < n_frames && w < nq_here) {
             const float den = sqrtf(vsum) * sqrtf(qn[w]);
-            scores[(int64_t)(q0 + w) * n_frames + f0 + fr] = den > 0.f ? dsum / den : 0.f;
+            scores[(int64_t)(q0 + w) * n_frames + f0 + fr] = den > 0.f ? dsum / den * inv_tau : 0.f;
         }
     }
 }
@@ -374,15 +374,20 @@ hipError_t expand_blocks_launch(const int32_t* block_idx, int n_questions, int k
 }
 
 hipError_t retrieve_launch(const RetrieveArgs& a, hipStream_t stream) {
-    const int d_prime = a.n_kv_heads * a.head_dim;
-    // token mean per query head: [n_questions, Hq * D] fp32, then the group mean: [n_questions, D']
-    hipError_t e = frame_keys_launch(a.q_question, a.n_questions, a.n_q_tokens, a.n_q_heads * a.head_dim,
-                                     a.dtype, a.q_heads, stream);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(group_mean_kernel, dim3((unsigned)a.n_questions, (unsigned)((d_prime + 255) / 256)),
-                       dim3(256), 0, stream, a.q_heads, a.n_q_heads, a.n_kv_heads, a.head_dim, a.q_vec);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    const int d_prime = a.dim > 0 ? a.dim : a.n_kv_heads * a.head_dim;
+    const float* q_vec = a.q_vec_given;
+    hipError_t e = hipSuccess;
+    if (!q_vec) {
+        // token mean per query head: [n_questions, Hq * D] fp32, then the group mean: [n_questions, D']
+        e = frame_keys_launch(a.q_question, a.n_questions, a.n_q_tokens, a.n_q_heads * a.head_dim,
+                              a.dtype, a.q_heads, stream);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(group_mean_kernel, dim3((unsigned)a.n_questions, (unsigned)((d_prime + 255) / 256)),
+                           dim3(256), 0, stream, a.q_heads, a.n_q_heads, a.n_kv_heads, a.head_dim, a.q_vec);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        q_vec = a.q_vec;
+    }
 
     // Many questions on one table: 8 frames x 8 questions per wavefront (if 8 question vectors
     // fit 48 KB of LDS).  One question per table: 4 frames per wavefront.
@@ -395,10 +400,10 @@ hipError_t retrieve_launch(const RetrieveArgs& a, hipStream_t stream) {
     const size_t lds = (size_t)qbt * (d_prime + 1) * sizeof(float);
     if (batched)
         hipLaunchKernelGGL((score_kernel<8, 8>), sg, dim3(SCORE_WAVES * 64), lds, stream, a.frame_keys,
-                           a.frame_keys_stride, a.n_frames, d_prime, a.q_vec, a.n_questions, a.scores);
+                           a.frame_keys_stride, a.n_frames, d_prime, q_vec, a.n_questions, a.inv_tau, a.scores);
     else
         hipLaunchKernelGGL((score_kernel<4, 1>), sg, dim3(SCORE_WAVES * 64), lds, stream, a.frame_keys,
-                           a.frame_keys_stride, a.n_frames, d_prime, a.q_vec, a.n_questions, a.scores);
+                           a.frame_keys_stride, a.n_frames, d_prime, q_vec, a.n_questions, a.inv_tau, a.scores);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
 

@@ -23,7 +23,7 @@ _DTYPES = {"f32": (REKV_F32, torch.float32), "bf16": (REKV_BF16, torch.bfloat16)
 # Every entry point include/rekv.h declares.
 SYMBOLS = ("rekv_create", "rekv_destroy", "rekv_last_error", "rekv_encode_chunk",
            "rekv_frame_keys", "rekv_retrieve_topk", "rekv_gather_kv", "rekv_qa_attention",
-           "rekv_decode_attention", "rekv_block_keys", "rekv_expand_blocks",
+           "rekv_decode_attention", "rekv_block_keys", "rekv_expand_blocks", "rekv_retrieve_external",
            "rekv_offload_kv", "rekv_offload_wait", "rekv_probe_copy", "rekv_probe_mfma")
 
 
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
                                  c_int32, c_void_p, c_void_p, c_void_p]
     L.rekv_qa_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p,
                                     c_int32, c_int32, c_void_p, c_void_p]
+    L.rekv_retrieve_external.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_int32, c_float,
+                                         c_int32, c_void_p, c_void_p, c_void_p, c_void_p]
     L.rekv_block_keys.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p]
     L.rekv_expand_blocks.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_void_p,
                                      c_void_p, c_void_p]
@@ -187,6 +189,22 @@ class Rekv:
             self._h, self._dev(frame_keys, torch.float32, name="frame_keys"), frame_keys_stride, n_frames,
             self._dev(q_question, last=(self.n_q_heads, self.head_dim), name="q_question"), nq, n_q_tokens, k,
             idx.data_ptr(), n_sel.data_ptr(), scores.data_ptr() if want_scores else None, _stream()))
+        return idx, n_sel, scores
+
+    def retrieve_external(self, frame_emb, q_emb, k: int, tau: float = 1.0, want_scores: bool = False):
+        """frame_emb [n_frames, dim] fp32, q_emb [n_questions, dim] fp32 -> (idx, n_sel, scores|None)."""
+        if frame_emb.dim() != 2 or q_emb.dim() != 2 or frame_emb.shape[1] != q_emb.shape[1]:
+            raise ValueError("frame_emb [n_frames, dim] and q_emb [n_questions, dim] must share dim")
+        n_frames, dim = frame_emb.shape
+        nq = q_emb.shape[0]
+        dev = q_emb.device
+        idx = torch.empty((nq, max(k, 0)), dtype=torch.int32, device=dev)
+        n_sel = torch.empty((nq,), dtype=torch.int32, device=dev)
+        scores = torch.empty((nq, n_frames), dtype=torch.float32, device=dev) if want_scores else None
+        self._check(self._lib.rekv_retrieve_external(
+            self._h, self._dev(frame_emb, torch.float32, name="frame_emb"), n_frames, dim,
+            self._dev(q_emb, torch.float32, name="q_emb"), nq, tau, k, idx.data_ptr(), n_sel.data_ptr(),
+            scores.data_ptr() if want_scores else None, _stream()))
         return idx, n_sel, scores
 
     def block_keys(self, frame_keys, n_frames: int, b: int, out=None):

@@ -28,7 +28,7 @@ def host(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def check_topk(idx_gpu, scores_oracle, k):
+def check_topk(idx_gpu, scores_oracle, k, gap=1e-3):
     """GPU selection vs the oracle's scores under the stated rule: exact where the k-th and
     (k+1)-th scores are more than 1e-3 apart; otherwise everything clearly above the cut is
     in, nothing clearly below it is."""
@@ -43,12 +43,12 @@ def check_topk(idx_gpu, scores_oracle, k):
         np.testing.assert_array_equal(got, np.arange(F))
         return
     srt = np.sort(scores_oracle)[::-1]
-    if srt[n - 1] - srt[n] > 1e-3:
+    if srt[n - 1] - srt[n] > gap:
         np.testing.assert_array_equal(got, ref)
     else:
         cut = srt[n - 1]
-        assert set(np.nonzero(scores_oracle > cut + 1e-3)[0]) <= set(got)
-        assert not (set(np.nonzero(scores_oracle < cut - 1e-3)[0]) & set(got))
+        assert set(np.nonzero(scores_oracle > cut + gap)[0]) <= set(got)
+        assert not (set(np.nonzero(scores_oracle < cut - gap)[0]) & set(got))
 
 
 # ----------------------------------------------------------------------------------------
@@ -197,6 +197,43 @@ def test_retrieval_matches_oracle(w, nq):
         planted = [p for p in W.planted_frames(w, i) if p < n_vis]
         assert set(planted) <= set(idx[i].tolist())
         assert int(n_sel[i]) == w.top_k
+
+
+# ----------------------------------------------------------------------------------------
+# external retrieval scoring (Eq. 2 with tau on given embeddings)
+# ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dim,n_frames,nq,tau,k", [(768, 3600, 1, 0.07, 64), (1152, 1000, 5, 0.01, 16),
+                                                   (64, 37, 9, 1.0, 50), (4, 3, 1, 2.5, 1)],
+                         ids=["768-hour", "1152-5q", "tiny-k>F", "dim4"])
+def test_external_retrieval_matches_oracle(dim, n_frames, nq, tau, k):
+    """Embeddings of the sizes a CLIP-like encoder pair gives, drawn at random with a few frames
+    pulled towards each question; scores and thresholds scale with 1 / tau."""
+    rng = np.random.default_rng(dim + n_frames)
+    emb = rng.standard_normal((n_frames, dim)).astype(np.float32)
+    qe = rng.standard_normal((nq, dim)).astype(np.float32)
+    for i in range(nq):
+        for f in rng.choice(n_frames, size=min(3, n_frames), replace=False):
+            emb[f] += 0.5 * qe[i]
+    if n_frames > 5:
+        emb[5] = 0.0                                                     # a zero-norm frame scores 0
+    r = Rekv.for_workload(W.C1)
+    idx, n_sel, scores = r.retrieve_external(torch.from_numpy(emb).to(DEV), torch.from_numpy(qe).to(DEV), k,
+                                             tau=tau, want_scores=True)
+    idx2, _, _ = r.retrieve_external(torch.from_numpy(emb).to(DEV), torch.from_numpy(qe).to(DEV), k, tau=tau)
+    assert torch.equal(idx, idx2)
+    for i in range(nq):
+        ref_idx, ref_s = O.retrieve_external(emb, qe[i], k, tau)
+        assert np.abs(host(scores)[i] - ref_s).max() < 1e-5 / tau
+        check_topk(idx[i].cpu().numpy(), ref_s, k, gap=1e-3 / tau)
+        np.testing.assert_array_equal(idx[i].cpu().numpy()[:min(k, n_frames)],
+                                      O.topk_frames(host(scores)[i], k))
+        assert int(n_sel[i]) == min(k, n_frames)
+        if n_frames > 5:
+            assert host(scores)[i][5] == 0.0
+    with pytest.raises(RekvError):
+        r.retrieve_external(torch.from_numpy(emb).to(DEV), torch.from_numpy(qe).to(DEV), k, tau=0.0)
+    with pytest.raises(RekvError):
+        r.retrieve_external(torch.zeros((4, 6), device=DEV), torch.zeros((1, 6), device=DEV), 1)   # dim % 4
 
 
 # ----------------------------------------------------------------------------------------

@@ -306,6 +306,18 @@ def test_topk_against_exhaustive_sort():
     np.testing.assert_array_equal(O.topk_frames([0.1, 0.9, 0.9, 0.5], 3), [1, 2, 3])
 
 
+def test_external_retrieval_is_temperature_scaled_cosine_ranking():
+    rng = np.random.default_rng(51)
+    emb, q = rng.standard_normal((40, 12)), rng.standard_normal(12)
+    idx, s = O.retrieve_external(emb, q, 7, tau=0.07)
+    ref = torch.nn.functional.cosine_similarity(torch.from_numpy(emb), torch.from_numpy(q)[None], dim=1).numpy()
+    np.testing.assert_allclose(s, ref / 0.07, rtol=1e-12)
+    np.testing.assert_array_equal(idx, np.sort(np.argsort(-ref, kind="stable")[:7]))
+    # a positive temperature never changes which frames are selected
+    np.testing.assert_array_equal(O.retrieve_external(emb, q, 7, tau=3.0)[0], idx)
+    np.testing.assert_array_equal(O.retrieve_external(emb, q, 7)[0], idx)
+
+
 def test_block_retrieval():
     F, nf, Hkv, D, Hq = 22, 3, 2, 4, 4
     k = _rand((F * nf, Hkv, D), 41)
