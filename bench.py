@@ -309,6 +309,20 @@ def main() -> None:
     o1 = torch.empty_like(q1)
     decode_us = timed_us(lambda: r.decode_attention(q1, gk[:nq], gv[:nq], kt, vt, n_text, out=o1))
     decode_bytes = 2 * nq * (w.top_k * nf + n_text) * d_prime * (2 if w.dtype == "bf16" else 4)
+    # QA attention of layer 0 with the retrieved frames read in place (no gathered copy), against
+    # gather + QA attention of the same questions
+    idx0 = idx[:nq].contiguous()
+    qa0 = torch.empty_like(d["qq"][:nq])
+    indexed_us = gathered_us = None
+    if not w.kv_on_host:
+        indexed_us = timed_us(lambda: r.attention_indexed(d["qq"][:nq], d["k"][0], d["v"][0], idx0, w.top_k,
+                                                           d["qk"][:nq], d["qv"][:nq], w.n_q_tokens,
+                                                           n_src_frames=F, out=qa0))
+
+        def gather_then_qa():
+            r.gather_kv(d["k"][0], d["v"][0], idx0, n_src_frames=F, dst_k=gk[:nq], dst_v=gv[:nq])
+            r.qa_attention(d["qq"][:nq], gk[:nq], gv[:nq], d["qk"][:nq], d["qv"][:nq], out=qa0)
+        gathered_us = timed_us(gather_then_qa)
     b_blk = 8
     kb = -(-w.top_k // b_blk)
     bk = torch.empty((-(-F // b_blk), d_prime), dtype=torch.float32, device="cuda:0")
@@ -369,6 +383,8 @@ def main() -> None:
         "planted_frames_retrieved": all(planted),
         "decode_step": {"us": decode_us, "kv_GBs": decode_bytes / decode_us / 1e3,
                         "what": f"{nq} question(s), 1 new token over {w.top_k * nf} retrieved + {n_text} text tokens, one layer"},
+        "qa_indexed": {"us": indexed_us, "gather_plus_qa_us": gathered_us,
+                       "what": "QA attention of one layer reading the retrieved frames in place vs gather + QA attention"},
         "block_retrieval": {"us": block_us, "b": b_blk, "blocks_selected": kb,
                             "what": "block vectors from the frame table + scores + top-k + frame list, one layer"},
         "box_peaks": dict(box_peaks(r, torch), encode_on_zero_inputs_TFLOPs=zero_tflops),

@@ -220,6 +220,27 @@ rekv_status rekv_decode_attention(rekv_ctx* ctx, const void* q, const void* k_re
                                   int32_t n_new_tokens, void* out, void* stream);
 
 /*
+ * Eq. 3 straight from the KV arena: the same attention as rekv_decode_attention (hence as
+ * rekv_qa_attention, which is its case n_new_tokens = n_text_tokens), but the retrieved KV is
+ * read in place through the frame list that retrieval produced, so the gathered copy is
+ * neither written nor read back.  The retrieved context of question i is the frames
+ * idx[i][0 .. n_ret_frames), in that order.
+ *
+ *   q, out          [n_questions, n_new_tokens, Hq, D]
+ *   k_src, v_src    [n_src_frames * N_f, Hkv, D] in HBM, each below 4 GiB
+ *   idx             [n_questions, idx_stride] int32 on the device, idx_stride >= n_ret_frames;
+ *                   the first n_ret_frames entries of every row must be frames of the arena
+ *                   (entries outside [0, n_src_frames) are clamped into it, never followed out
+ *                   of bounds); 1 <= n_ret_frames <= 1024
+ *   k_text, v_text, text_stride, n_text_tokens, n_new_tokens   as in rekv_decode_attention
+ */
+rekv_status rekv_attention_indexed(rekv_ctx* ctx, const void* q, const void* k_src, const void* v_src,
+                                   int32_t n_src_frames, const int32_t* idx, int64_t idx_stride,
+                                   int32_t n_ret_frames, const void* k_text, const void* v_text,
+                                   int64_t text_stride, int32_t n_text_tokens, int32_t n_questions,
+                                   int32_t n_new_tokens, void* out, void* stream);
+
+/*
  * Offload of encoded KV to RAM (the paper stores all video KV and moves what leaves the
  * local window off the GPU).  Copies n_frames whole frames of K and V, starting at frame
  * first_frame of the device arrays, to the same frame positions of the pinned host arrays.

@@ -212,6 +212,45 @@ rekv_status rekv_decode_attention(rekv_ctx* c, const void* q, const void* k_ret,
     return run_attention(c, p, static_cast<hipStream_t>(stream));
 }
 
+rekv_status rekv_attention_indexed(rekv_ctx* c, const void* q, const void* k_src, const void* v_src,
+                                   int32_t n_src_frames, const int32_t* idx, int64_t idx_stride,
+                                   int32_t n_ret_frames, const void* k_text, const void* v_text,
+                                   int64_t text_stride, int32_t n_text_tokens, int32_t n_questions,
+                                   int32_t n_new_tokens, void* out, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!q || !k_src || !v_src || !idx || !k_text || !v_text || !out)
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_attention_indexed: null pointer");
+    if (!aligned16(q) || !aligned16(k_src) || !aligned16(v_src) || !aligned16(k_text) || !aligned16(v_text) || !aligned16(out))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_attention_indexed: pointers must be 16-byte aligned");
+    if (n_src_frames <= 0 || n_ret_frames <= 0 || idx_stride < n_ret_frames || n_questions <= 0 ||
+        n_new_tokens <= 0 || n_text_tokens < n_new_tokens || text_stride < n_text_tokens)
+        return fail(c, REKV_ERR_INVALID_ARG,
+                    "rekv_attention_indexed: n_src_frames=%d n_ret_frames=%d idx_stride=%lld n_questions=%d n_new_tokens=%d "
+                    "n_text_tokens=%d text_stride=%lld", n_src_frames, n_ret_frames, (long long)idx_stride, n_questions,
+                    n_new_tokens, n_text_tokens, (long long)text_stride);
+    const int64_t n_f = c->shape.tokens_per_frame;
+    const int64_t row_bytes = (int64_t)c->shape.n_kv_heads * c->shape.head_dim * (int64_t)elem_size(c);
+    if (n_ret_frames > 1024 || n_ret_frames * n_f >= (1 << 23))
+        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_attention_indexed: at most 1024 frames and 2^23 - 1 tokens per question (got %d frames)",
+                    n_ret_frames);
+    if ((int64_t)n_src_frames * n_f * row_bytes > 0xFFF00000LL)
+        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_attention_indexed: the K (and V) arena must stay below 4 GiB (%d frames of %lld bytes)",
+                    n_src_frames, (long long)(n_f * row_bytes));
+    if ((int64_t)n_new_tokens * (c->shape.n_q_heads / c->shape.n_kv_heads) > 0x3FFFFFFF)
+        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_attention_indexed: %d new tokens are too many", n_new_tokens);
+    rekv::AttnProblem p;
+    memset(&p, 0, sizeof(p));
+    p.q = q; p.out = out;
+    p.k_a = k_src; p.v_a = v_src; p.k_b = k_text; p.v_b = v_text;
+    p.len_a = (int32_t)(n_ret_frames * n_f); p.len_b = n_text_tokens; p.len_q = n_new_tokens;
+    p.b_stride = text_stride;
+    p.n_items = n_questions; p.is_encode = 0;
+    p.n_q_heads = c->shape.n_q_heads; p.n_kv_heads = c->shape.n_kv_heads; p.head_dim = c->shape.head_dim;
+    p.scale = c->scale;
+    p.a_index = idx; p.a_index_stride = idx_stride; p.n_f = (int32_t)n_f; p.n_src_frames = n_src_frames;
+    return run_attention(c, p, static_cast<hipStream_t>(stream));
+}
+
 rekv_status rekv_frame_keys(rekv_ctx* c, const void* k, int32_t n_frames, float* frame_keys, void* stream) {
     if (!c) return REKV_ERR_INVALID_ARG;
     if (!k || !frame_keys) return fail(c, REKV_ERR_INVALID_ARG, "rekv_frame_keys: null pointer");

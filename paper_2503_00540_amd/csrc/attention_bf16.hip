@@ -126,9 +126,14 @@ using IC = std::integral_constant<int, I>;
 
 // ENCODE selects the segment layout (Eq. 1 window + chunk in one cache, or Eq. 3 retrieved KV +
 // question) at compile time; the two instantiations also show up under separate names in a trace.
-template <int D, bool ENCODE>
+// INDEXED: segment A is read from the KV arena through a frame index list (no gathered copy).
+constexpr int MAX_INDEXED_FRAMES = 1024;   // index entries staged in LDS per workgroup
+
+template <int D, bool ENCODE, bool INDEXED>
 __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
+    static_assert(!(ENCODE && INDEXED), "the encode window is contiguous");
     typedef Cfg<D> C;
+    __shared__ int32_t frame_of_slot[INDEXED ? MAX_INDEXED_FRAMES : 1];
     // K stages 0..3, then V stages 0..3; one array so that every stage is a constant offset
     __shared__ __attribute__((aligned(1024))) bf16_t lds[2 * STAGES * C::TILE_ELEMS];
     constexpr uint32_t TILE_B = C::TILE_ELEMS * 2;           // bytes per stage
@@ -215,6 +220,34 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
         }
     }
 
+    // Indexed segment A: the index row of this item, clamped into the arena, staged in LDS.
+    const float inv_n_f = INDEXED ? 1.f / (float)p.n_f : 0.f;
+    if (INDEXED) {
+        const int n_slots = (seg.len_a + p.n_f - 1) / p.n_f;
+        for (int i = tid; i < n_slots; i += THREADS) {
+            int f = p.a_index[(int64_t)item * p.a_index_stride + i];
+            f = f < 0 ? 0 : (f < p.n_src_frames ? f : p.n_src_frames - 1);
+            frame_of_slot[i] = f;
+        }
+        __syncthreads();
+    }
+    // A tile of the indexed segment A (t < tiles_a): every lane looks up the frame of its row.
+    // Rows are below 2^23, so the float quotient is off by at most one and is corrected exactly.
+    auto dma_indexed = [&](const char* arena, int t, uint32_t stage_b) {
+        const int key0 = t * BN;
+        const int n_valid = seg.len_a - key0;
+#pragma unroll
+        for (int j = 0; j < C::DMA_PER_WAVE; ++j) {
+            int r = dma_row + j * C::RPI;
+            r = (r < n_valid - 1 ? r : n_valid - 1) + key0;
+            int slot = (int)((float)r * inv_n_f);
+            int within = r - slot * p.n_f;
+            if (within < 0) { --slot; within += p.n_f; }
+            if (within >= p.n_f) { ++slot; within -= p.n_f; }
+            const uint32_t src_row = (uint32_t)(frame_of_slot[slot] * p.n_f + within);
+            dma16(arena, src_row * row_stride_b + dma_coff[j], dma_lds + stage_b + j * 1024u);
+        }
+    };
     // A whole tile inside segment A: constant per-lane offsets, only the base moves.
     auto dma_fast = [&](const char* base, uint32_t stage_b) {
 #pragma unroll
@@ -228,6 +261,10 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     auto dma_any = [&](const char* seg_a, const char* seg_b, int t, uint32_t stage_b) {
         t = t < t_end - 1 ? t : t_end - 1;
         const bool in_b = t >= tiles_a;
+        if (INDEXED && !in_b) {
+            dma_indexed(seg_a, t, stage_b);
+            return;
+        }
         const int key0 = (in_b ? t - tiles_a : t) * BN;
         const int n_valid = (in_b ? p.len_b : seg.len_a) - key0;
         const char* base = (in_b ? seg_b : seg_a) + (int64_t)key0 * row_stride_b;
@@ -285,7 +322,10 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
         constexpr uint32_t KN = decltype(kn)::value * TILE_B, KL = decltype(kl)::value * TILE_B;
         constexpr uint32_t VC = decltype(vc)::value * TILE_B, VL = decltype(vl)::value * TILE_B;
         constexpr bool PLAIN = decltype(plain)::value;
-        if (PLAIN) {
+        if (PLAIN && INDEXED) {
+            dma_indexed(ka, t + 4, KL);
+            dma_indexed(va, t + 3, STAGES * TILE_B + VL);
+        } else if (PLAIN) {
             dma_fast(k_run, KL);
             dma_fast(v_run, STAGES * TILE_B + VL);
             k_run += tile_stride_b;
@@ -550,9 +590,11 @@ hipError_t launch(const AttnProblem& p, const AttnPlan& plan, void* workspace, h
     }
     const int64_t nb = ik * plan.n_splits * plan.m_tiles;
     if (p.is_encode)
-        hipLaunchKernelGGL((attn_bf16_kernel<D, true>), dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
+        hipLaunchKernelGGL((attn_bf16_kernel<D, true, false>), dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
+    else if (p.a_index)
+        hipLaunchKernelGGL((attn_bf16_kernel<D, false, true>), dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
     else
-        hipLaunchKernelGGL((attn_bf16_kernel<D, false>), dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
+        hipLaunchKernelGGL((attn_bf16_kernel<D, false, false>), dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (plan.n_splits > 1) {

@@ -45,6 +45,14 @@ __global__ __launch_bounds__(ROWS_PER_BLOCK * 64) void attn_f32_kernel(AttnProbl
     __builtin_amdgcn_wave_barrier();
 
     float o[MAX_D / 64] = {0.f, 0.f, 0.f, 0.f};
+    // row of segment A's token j in k_a / v_a: j itself, or through the frame index list
+    auto a_row = [&](int j) -> int64_t {
+        if (!p.a_index) return j;
+        const int slot = j / p.n_f;
+        int f = p.a_index[(int64_t)item * p.a_index_stride + slot];
+        f = f < 0 ? 0 : (f < p.n_src_frames ? f : p.n_src_frames - 1);
+        return (int64_t)f * p.n_f + (j - slot * p.n_f);
+    };
     float m = -INFINITY, l = 0.f;
     const int n_vis_b = tok + (p.len_b - p.len_q) + 1;   // causal part: text tokens up to itself
     const int n_keys = seg.len_a + n_vis_b;
@@ -53,7 +61,7 @@ __global__ __launch_bounds__(ROWS_PER_BLOCK * 64) void attn_f32_kernel(AttnProbl
         float s = -INFINITY;
         const float* vrow = nullptr;
         if (j < n_keys) {
-            const float* krow = j < seg.len_a ? ka + (int64_t)j * row_stride
+            const float* krow = j < seg.len_a ? ka + a_row(j) * row_stride
                                               : kb + (int64_t)(j - seg.len_a) * row_stride;
             float acc = 0.f;
             for (int d = 0; d < D; d += 4) {
@@ -77,7 +85,7 @@ __global__ __launch_bounds__(ROWS_PER_BLOCK * 64) void attn_f32_kernel(AttnProbl
         const int cnt = n_keys - j0 < 64 ? n_keys - j0 : 64;
         for (int jj = 0; jj < cnt; ++jj) {
             const int jk = j0 + jj;
-            vrow = jk < seg.len_a ? va + (int64_t)jk * row_stride
+            vrow = jk < seg.len_a ? va + a_row(jk) * row_stride
                                   : vb + (int64_t)(jk - seg.len_a) * row_stride;
             const float pv = p_lds[wave][jj];
 #pragma unroll

@@ -34,6 +34,12 @@ struct AttnProblem {
     int32_t is_encode;
     int32_t n_q_heads, n_kv_heads, head_dim;
     float scale;
+    // Indexed segment A (QA / decode straight from the KV arena, no gathered copy): A-token j of
+    // item i is token a_index[i * a_index_stride + j / n_f] * n_f + j % n_f of k_a / v_a.
+    const int32_t* a_index;   // NULL: segment A is contiguous
+    int64_t a_index_stride;
+    int32_t n_f;              // tokens per frame
+    int32_t n_src_frames;     // frames in the arena; index entries are clamped into [0, n_src_frames)
 };
 
 // Resolves one item's segment bases (in elements) and lengths.  Host and device.
@@ -50,7 +56,7 @@ __host__ __device__ inline ItemSegs item_segments(const AttnProblem& p, int item
         s.b_off = t0;
         s.len_a = (int32_t)(t0 - w0);
     } else {
-        s.a_off = (int64_t)item * p.len_a;
+        s.a_off = p.a_index ? 0 : (int64_t)item * p.len_a;
         s.b_off = (int64_t)item * p.b_stride;
         s.len_a = p.len_a;
     }

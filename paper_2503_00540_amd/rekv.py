@@ -23,7 +23,7 @@ _DTYPES = {"f32": (REKV_F32, torch.float32), "bf16": (REKV_BF16, torch.bfloat16)
 # Every entry point include/rekv.h declares.
 SYMBOLS = ("rekv_create", "rekv_destroy", "rekv_last_error", "rekv_encode_chunk",
            "rekv_frame_keys", "rekv_retrieve_topk", "rekv_gather_kv", "rekv_qa_attention",
-           "rekv_decode_attention", "rekv_block_keys", "rekv_expand_blocks", "rekv_retrieve_external",
+           "rekv_decode_attention", "rekv_block_keys", "rekv_expand_blocks", "rekv_retrieve_external", "rekv_attention_indexed",
            "rekv_offload_kv", "rekv_offload_wait", "rekv_probe_copy", "rekv_probe_mfma")
 
 
@@ -72,6 +72,9 @@ def lib() -> ctypes.CDLL:
                                      c_void_p, c_void_p]
     L.rekv_decode_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p,
                                         c_int64, c_int32, c_int32, c_int32, c_void_p, c_void_p]
+    L.rekv_attention_indexed.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_int64,
+                                         c_int32, c_void_p, c_void_p, c_int64, c_int32, c_int32, c_int32,
+                                         c_void_p, c_void_p]
     L.rekv_offload_kv.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32,
                                   c_void_p]
     L.rekv_offload_wait.argtypes = [c_void_p]
@@ -302,6 +305,32 @@ class Rekv:
             self._dev(v_ret, last=kh, name="v_ret") if n_ret else None, n_ret,
             self._dev(k_text, last=kh, name="k_text"), self._dev(v_text, last=kh, name="v_text"),
             stride, n_text_tokens, nq, n_new, self._dev(out, last=qh, name="out"), _stream()))
+        return out
+
+    def attention_indexed(self, q, k_src, v_src, idx, n_ret_frames: int, k_text, v_text, n_text_tokens: int,
+                          n_src_frames: int | None = None, out=None):
+        """Eq. 3 with the retrieved KV read in place: q [n_questions, n_new, Hq, D]; k_src/v_src the
+        arena [tokens, Hkv, D]; idx [n_questions, >= n_ret_frames] int32; k_text/v_text
+        [n_questions, text_stride, Hkv, D]."""
+        qh, kh = (self.n_q_heads, self.head_dim), (self.n_kv_heads, self.head_dim)
+        if q.dim() != 4 or k_text.dim() != 4 or idx.dim() != 2 or idx.dtype != torch.int32:
+            raise ValueError("q, k_text must be 4-d; idx [n_questions, slots] int32")
+        nq, n_new = q.shape[0], q.shape[1]
+        if idx.shape[0] != nq or k_text.shape[0] != nq or v_text.shape != k_text.shape:
+            raise ValueError("idx, k_text, v_text must have one row per question")
+        nf = k_src.shape[0] // self.tokens_per_frame if n_src_frames is None else n_src_frames
+        if k_src.shape[0] < nf * self.tokens_per_frame or v_src.shape != k_src.shape:
+            raise ValueError("k_src / v_src are shorter than n_src_frames frames")
+        out = torch.empty_like(q) if out is None else out
+        if out.shape != q.shape:
+            raise ValueError("out must have the shape of q")
+        if not idx.is_cuda or not idx.is_contiguous():
+            raise ValueError("idx must be a contiguous device tensor")
+        self._check(self._lib.rekv_attention_indexed(
+            self._h, self._dev(q, last=qh, name="q"), self._dev(k_src, last=kh, name="k_src"),
+            self._dev(v_src, last=kh, name="v_src"), nf, idx.data_ptr(), idx.shape[1], n_ret_frames,
+            self._dev(k_text, last=kh, name="k_text"), self._dev(v_text, last=kh, name="v_text"),
+            k_text.shape[1], n_text_tokens, nq, n_new, self._dev(out, last=qh, name="out"), _stream()))
         return out
 
     def offload_kv(self, dev_k, dev_v, host_k, host_v, first_frame: int, n_frames: int):

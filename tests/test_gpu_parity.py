@@ -478,6 +478,55 @@ def test_decode_attention_matches_oracle(w, nq, n_ret_frames, n_gen, n_new, slac
         assert err < TOL[w.dtype], (i, err)
 
 
+@pytest.mark.parametrize("w,nq,n_ret_frames,n_gen,n_new", [
+    (W.C1, 1, 16, 0, None), (W.C1, 2, 16, 40, 1), (W.C4.scaled(n_q_tokens=17), 5, 7, 3, 2),
+    (W.C1.scaled(tokens_per_frame=12, name="C1-12"), 3, 37, 0, None), (W.C2, 1, 64, 128, 1),
+    (W.C0.scaled(tokens_per_frame=7, name="C0i"), 2, 5, 4, 2)],
+    ids=["7B-prefill", "7B-decode", "72B-5q", "12-token-frames", "hour-k64-decode", "f32"])
+def test_indexed_attention_matches_oracle_and_the_gathered_path(w, nq, n_ret_frames, n_gen, n_new):
+    """Eq. 3 with the retrieved frames read in place through the index list: against the oracle
+    (gather, then attention) and against this library's own gather + attention.  Frame lists
+    are unsorted picks from a larger arena; the index rows are wider than the frames used and
+    padded with -1."""
+    w = w.scaled(n_frames=3 * n_ret_frames + 5)
+    r = Rekv.for_workload(w)
+    k, v = W.frames_k(w, 0, w.n_frames), W.frames_v(w, 0, w.n_frames)
+    nf = w.tokens_per_frame
+    n_text = w.n_q_tokens + n_gen
+    n_new = n_text if n_new is None else n_new
+    rng = np.random.default_rng(5)
+    idx = np.full((nq, n_ret_frames + 3), -1, dtype=np.int32)
+    qs, kts, vts = [], [], []
+    for i in range(nq):
+        idx[i, :n_ret_frames] = rng.choice(w.n_frames, size=n_ret_frames, replace=False)
+        parts = [W.question_qkv(w, i + 64 * j) for j in range(1 + (n_gen + w.n_q_tokens - 1) // w.n_q_tokens)]
+        qt, kt, vt = (np.concatenate([p[c] for p in parts])[:n_text] for c in range(3))
+        qs.append(qt[n_text - n_new:]); kts.append(kt); vts.append(vt)
+    dk, dv = dev(k, w), dev(v, w)
+    didx = torch.from_numpy(idx).to(DEV)
+    dq, dkt, dvt = dev(np.stack(qs), w), dev(np.stack(kts), w), dev(np.stack(vts), w)
+    out = r.attention_indexed(dq, dk, dv, didx, n_ret_frames, dkt, dvt, n_text)
+    gk, gv = r.gather_kv(dk, dv, didx[:, :n_ret_frames].contiguous())
+    via_gather = r.decode_attention(dq, gk, gv, dkt, dvt, n_text)
+    assert (out.float() - via_gather.float()).abs().max().item() < 1e-6 + (4e-3 if w.dtype == "bf16" else 0)
+    out = host(out)
+    for i in range(nq):
+        rk, rv = O.gather_kv(k, v, idx[i, :n_ret_frames], nf)
+        ref = O.decode_attention(qs[i], rk, rv, kts[i], vts[i])
+        err = np.abs(out[i] - ref).max()
+        assert err < TOL[w.dtype], (i, err)
+    # an entry outside the arena is clamped into it, never followed
+    bad = didx.clone()
+    bad[0, 0] = 2_000_000_000
+    good = didx.clone()
+    good[0, 0] = w.n_frames - 1
+    a = r.attention_indexed(dq, dk, dv, bad, n_ret_frames, dkt, dvt, n_text)
+    b = r.attention_indexed(dq, dk, dv, good, n_ret_frames, dkt, dvt, n_text)
+    assert torch.equal(a, b)
+    with pytest.raises(RekvError):
+        r.attention_indexed(dq, dk, dv, didx, n_ret_frames + 4, dkt, dvt, n_text)     # wider than the index rows
+
+
 def test_decode_attention_rejects_bad_arguments():
     w = W.C1
     r = Rekv.for_workload(w)
