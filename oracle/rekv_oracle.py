@@ -134,6 +134,64 @@ def gather_kv(k, v, frames, tokens_per_frame):
     return np.asarray(k)[rows], np.asarray(v)[rows]
 
 
+def apply_rope(x, positions, base=10000.0, layout="half"):
+    """Rotary position embedding (the paper's positional-encoding paragraph cites RoFormer):
+    every head vector is split into D/2 pairs; pair i is rotated by the angle
+    position * theta_i, theta_i = base^(-2i/D):
+        a' = a cos - b sin,   b' = a sin + b cos.
+    layout "interleaved" pairs dims (2i, 2i+1) as RoFormer writes it; "half" pairs dims
+    (i, i + D/2), the arrangement of the decoder family the paper runs on.  Positions may be
+    any integers (negative ones rotate back).
+
+    x [T, H, D], positions [T] -> [T, H, D] fp64.
+    """
+    x = _f64(x)
+    t, _, d = x.shape
+    half = d // 2
+    theta = np.array([base ** (-2.0 * i / d) for i in range(half)])
+    ang = np.asarray(positions, dtype=np.float64).reshape(t, 1, 1) * theta.reshape(1, 1, half)
+    c, s_ = np.cos(ang), np.sin(ang)
+    out = np.empty_like(x)
+    if layout == "interleaved":
+        a, b = x[..., 0::2], x[..., 1::2]
+        out[..., 0::2] = a * c - b * s_
+        out[..., 1::2] = a * s_ + b * c
+    elif layout == "half":
+        a, b = x[..., :half], x[..., half:]
+        out[..., :half] = a * c - b * s_
+        out[..., half:] = a * s_ + b * c
+    else:
+        raise ValueError(layout)
+    return out
+
+
+def gather_kv_rope(k, v, frames, tokens_per_frame, mode="consecutive", pos_offset=0,
+                   src_rotated=False, src_pos_offset=0, base=10000.0, layout="half"):
+    """Retrieved KV with the paper's position policy for question answering: the original
+    positions of the retrieved tokens are dropped and the tokens are treated as regular
+    consecutive tokens (mode "consecutive": gathered token j gets position pos_offset + j);
+    the static variant gives every retrieved token the same position (mode "static":
+    pos_offset).  Values carry no position.
+
+    The cache may hold keys without positions (src_rotated False) or keys already rotated
+    at their stream position src_pos_offset + token index (True); rotations compose, so the
+    latter are turned by the difference of the two positions.
+    Returns (K' [len(frames) * N_f, Hkv, D] fp64, V likewise)."""
+    rk, rv = gather_kv(k, v, frames, tokens_per_frame)
+    n = rk.shape[0]
+    new_pos = np.full(n, pos_offset, dtype=np.int64)
+    if mode == "consecutive":
+        new_pos = new_pos + np.arange(n)
+    elif mode != "static":
+        raise ValueError(mode)
+    old_pos = np.zeros(n, dtype=np.int64)
+    if src_rotated:
+        old_pos = src_pos_offset + np.concatenate(
+            [np.arange(int(f) * tokens_per_frame, (int(f) + 1) * tokens_per_frame) for f in frames]
+        ).astype(np.int64) if len(frames) else old_pos
+    return apply_rope(rk, new_pos - old_pos, base, layout), _f64(rv)
+
+
 def qa_attention(q, k_ret, v_ret, k_self, v_self, scale=None, return_probs=False):
     """Eq. 3 for X = the question tokens: every question token attends to all of the
     retrieved KV R and, causally, to the question tokens up to itself.  The local

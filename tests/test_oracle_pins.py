@@ -367,6 +367,80 @@ def test_block_whose_frames_match_the_question_ranks_first():
     assert abs(sc[2] - 1.0) < 1e-12
 
 
+# ----------------------------------------------------------------------------------
+# rotary positions of the retrieved KV
+# ----------------------------------------------------------------------------------
+@pytest.mark.parametrize("layout", ["half", "interleaved"])
+def test_rope_against_complex_rotation_and_its_defining_properties(layout):
+    T, H, D = 7, 3, 8
+    x, y = _rand((T, H, D), 61), _rand((T, H, D), 62)
+    pos = np.array([0, 1, 2, 5, 17, -3, 100000])
+    got = O.apply_rope(x, pos, base=10000.0, layout=layout)
+    # independent formulation: each pair is a complex number multiplied by exp(i * pos * theta_i)
+    theta = 10000.0 ** (-np.arange(D // 2) * 2.0 / D)
+    z = (x[..., 0::2] + 1j * x[..., 1::2]) if layout == "interleaved" else (x[..., :D // 2] + 1j * x[..., D // 2:])
+    zr = z * np.exp(1j * pos[:, None, None] * theta[None, None, :])
+    want = np.empty_like(x)
+    if layout == "interleaved":
+        want[..., 0::2], want[..., 1::2] = zr.real, zr.imag
+    else:
+        want[..., :D // 2], want[..., D // 2:] = zr.real, zr.imag
+    np.testing.assert_allclose(got, want, atol=1e-9)
+    np.testing.assert_allclose(got[0], x[0], atol=0)                       # position 0 is the identity
+    np.testing.assert_allclose(np.linalg.norm(got, axis=-1), np.linalg.norm(x, axis=-1), rtol=1e-12)
+    # relative: <R(m) q, R(n) k> depends on m - n only
+    m, n = np.array([9] * T), np.array([4] * T)
+    lhs = (O.apply_rope(x, m, layout=layout) * O.apply_rope(y, n, layout=layout)).sum(-1)
+    rhs = (O.apply_rope(x, m - n, layout=layout) * y).sum(-1)
+    np.testing.assert_allclose(lhs, rhs, atol=1e-10)
+    # rotations compose, and a negative position undoes a positive one
+    np.testing.assert_allclose(O.apply_rope(O.apply_rope(x, m, layout=layout), n, layout=layout),
+                               O.apply_rope(x, m + n, layout=layout), atol=1e-10)
+    np.testing.assert_allclose(O.apply_rope(O.apply_rope(x, pos, layout=layout), -pos, layout=layout), x, atol=1e-7)
+
+
+def test_rope_by_hand_two_dims():
+    # D = 2: one pair, theta_0 = 1, position p rotates the plane by p radians
+    x = np.array([[[1.0, 0.0]], [[0.0, 2.0]]])
+    got = O.apply_rope(x, [math.pi / 2, math.pi / 6], layout="half")
+    np.testing.assert_allclose(got[0, 0], [0.0, 1.0], atol=1e-15)
+    np.testing.assert_allclose(got[1, 0], [-1.0, math.sqrt(3.0)], atol=1e-15)
+    # D = 4, base 100: theta = (1, 0.1); the two layouts differ only in which dims pair up
+    v = np.array([[[1.0, 2.0, 3.0, 4.0]]])
+    h = O.apply_rope(v, [3], base=100.0, layout="half")[0, 0]
+    i = O.apply_rope(v, [3], base=100.0, layout="interleaved")[0, 0]
+    c0, s0, c1, s1 = math.cos(3.0), math.sin(3.0), math.cos(0.3), math.sin(0.3)
+    np.testing.assert_allclose(h, [1 * c0 - 3 * s0, 2 * c1 - 4 * s1, 1 * s0 + 3 * c0, 2 * s1 + 4 * c1], atol=1e-14)
+    np.testing.assert_allclose(i, [1 * c0 - 2 * s0, 1 * s0 + 2 * c0, 3 * c1 - 4 * s1, 3 * s1 + 4 * c1], atol=1e-14)
+
+
+def test_gather_with_position_policy():
+    F, nf, Hkv, D = 9, 3, 2, 8
+    k, v = _rand((F * nf, Hkv, D), 63), _rand((F * nf, Hkv, D), 64)
+    frames = [7, 2, 3]
+    rk, rv = O.gather_kv(k, v, frames, nf)
+    # consecutive: gathered token j sits at position offset + j, whatever frame it came from
+    gk, gv = O.gather_kv_rope(k, v, frames, nf, mode="consecutive", pos_offset=5)
+    np.testing.assert_array_equal(gv, rv)
+    np.testing.assert_allclose(gk, O.apply_rope(rk, 5 + np.arange(3 * nf)), atol=1e-12)
+    # static: one position for all; position 0 leaves the keys as cached
+    gk, _ = O.gather_kv_rope(k, v, frames, nf, mode="static", pos_offset=11)
+    np.testing.assert_allclose(gk, O.apply_rope(rk, np.full(3 * nf, 11)), atol=1e-12)
+    np.testing.assert_allclose(O.gather_kv_rope(k, v, frames, nf, mode="static")[0], rk, atol=0)
+    # a cache that stores keys rotated at their stream position gives the same result
+    k_rot = O.apply_rope(k, 40 + np.arange(F * nf))
+    for mode in ("consecutive", "static"):
+        a, _ = O.gather_kv_rope(k, v, frames, nf, mode=mode, pos_offset=5)
+        b, _ = O.gather_kv_rope(k_rot, v, frames, nf, mode=mode, pos_offset=5, src_rotated=True, src_pos_offset=40)
+        np.testing.assert_allclose(a, b, atol=1e-9)
+    # attention scores between consecutive-position keys and a query at position p see only p - j
+    q = _rand((1, Hkv, D), 65)
+    gk, _ = O.gather_kv_rope(k, v, frames, nf, mode="consecutive")
+    s1 = (O.apply_rope(q, [20]) * gk[4:5]).sum(-1)
+    s2 = (O.apply_rope(q, [16]) * rk[4:5]).sum(-1)
+    np.testing.assert_allclose(s1, s2, atol=1e-10)
+
+
 def test_gather():
     F, Nf, Hkv, D = 9, 4, 2, 3
     k, v = _rand((F * Nf, Hkv, D), 41), _rand((F * Nf, Hkv, D), 42)
