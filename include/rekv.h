@@ -189,6 +189,29 @@ rekv_status rekv_gather_kv(rekv_ctx* ctx, const void* src_k, const void* src_v,
                            int32_t n_questions, int32_t k, void* dst_k, void* dst_v, void* stream);
 
 /*
+ * Reload of the retrieved KV with the position policy of the positional-encoding paragraph:
+ * for question answering the original positions of the retrieved tokens are dropped and the
+ * tokens count as regular consecutive tokens; the static variant gives all of them one
+ * position.  Values are copied as by rekv_gather_kv; keys are rotated (rotary position
+ * embedding: pair i of a head vector turns by position * base^(-2i/D)) to
+ *   pos_mode 0 (consecutive): position pos_offset + j for gathered token j of the question,
+ *   pos_mode 1 (static):      position pos_offset for every token.
+ * The cache may hold keys without positions (src_rotated = 0) or keys already rotated at
+ * their stream position src_pos_offset + token index (src_rotated = 1); those are turned by
+ * the difference.  rope_layout 0 pairs dims (i, i + D/2), 1 pairs dims (2i, 2i + 1).
+ * Angles are formed and range-reduced in double precision.
+ *
+ *   src_k, src_v, idx, dst_k, dst_v, n_src_frames, n_questions, k   as in rekv_gather_kv,
+ *                 source in HBM only; entries of idx outside the arena zero-fill their block
+ *   rope_base     > 1 (10000 in RoFormer)
+ *   D             a multiple of 16 (bf16) or 8 (fp32), at most 256
+ */
+rekv_status rekv_gather_kv_rope(rekv_ctx* ctx, const void* src_k, const void* src_v, int32_t n_src_frames,
+                                const int32_t* idx, int32_t n_questions, int32_t k, void* dst_k, void* dst_v,
+                                double rope_base, int32_t rope_layout, int32_t pos_mode, int64_t pos_offset,
+                                int32_t src_rotated, int64_t src_pos_offset, void* stream);
+
+/*
  * Question answering over the retrieved KV, Eq. 3 with X = the question tokens: every
  * question token attends to all n_ret_tokens retrieved tokens and, causally, to the
  * question tokens up to itself.

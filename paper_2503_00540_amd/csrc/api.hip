@@ -432,6 +432,36 @@ rekv_status rekv_gather_kv(rekv_ctx* c, const void* src_k, const void* src_v, in
     return e == hipSuccess ? REKV_OK : fail_hip(c, "rekv_gather_kv: host copies", e);
 }
 
+rekv_status rekv_gather_kv_rope(rekv_ctx* c, const void* src_k, const void* src_v, int32_t n_src_frames,
+                                const int32_t* idx, int32_t n_questions, int32_t k, void* dst_k, void* dst_v,
+                                double rope_base, int32_t rope_layout, int32_t pos_mode, int64_t pos_offset,
+                                int32_t src_rotated, int64_t src_pos_offset, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!src_k || !src_v || !idx || !dst_k || !dst_v) return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_rope: null pointer");
+    if (!aligned16(src_k) || !aligned16(src_v) || !aligned16(dst_k) || !aligned16(dst_v))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_rope: pointers must be 16-byte aligned");
+    if (n_src_frames <= 0 || n_questions <= 0 || k <= 0 || (int64_t)n_questions * k > 0x7FFFFFFF)
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_rope: n_src_frames=%d n_questions=%d k=%d", n_src_frames, n_questions, k);
+    if (!(rope_base > 1.0) || !(rope_base < 1e30) || (rope_layout != 0 && rope_layout != 1) ||
+        (pos_mode != 0 && pos_mode != 1) || (src_rotated != 0 && src_rotated != 1))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_rope: rope_base=%g (> 1) rope_layout=%d pos_mode=%d src_rotated=%d (each 0 or 1)",
+                    rope_base, rope_layout, pos_mode, src_rotated);
+    const int d = c->shape.head_dim, epc = c->shape.dtype == REKV_BF16 ? 8 : 4;
+    if (d > 256 || d % (2 * epc) != 0)
+        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_gather_kv_rope: head_dim=%d must be a multiple of %d, at most 256", d, 2 * epc);
+    const int64_t span = (int64_t)1 << 40;     // positions far below 2^53 keep the double-precision angle exact
+    if (pos_offset < -span || pos_offset > span || src_pos_offset < -span || src_pos_offset > span)
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_rope: position offsets must lie within +-2^40");
+    rekv::RopeArgs ra;
+    ra.log2_base = log2(rope_base);
+    ra.pos_offset = pos_offset; ra.src_pos_offset = src_pos_offset;
+    ra.is_static = pos_mode; ra.src_rotated = src_rotated; ra.interleaved = rope_layout;
+    hipError_t e = rekv::gather_rope_launch(src_k, src_v, n_src_frames, idx, n_questions, k, c->shape.tokens_per_frame,
+                                            c->shape.n_kv_heads, d, c->shape.dtype, dst_k, dst_v, ra,
+                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "gather_kv_rope launch", e);
+}
+
 rekv_status rekv_offload_kv(rekv_ctx* c, const void* dev_k, const void* dev_v, void* host_k, void* host_v,
                             int64_t first_frame, int32_t n_frames, void* stream_) {
     if (!c) return REKV_ERR_INVALID_ARG;

@@ -106,6 +106,18 @@ hipError_t gather_launch(const void* src_k, const void* src_v, int n_src_frames,
                          int n_blocks, size_t frame_bytes, void* dst_k, void* dst_v,
                          hipStream_t stream);
 
+// Position policy of the retrieved keys (gather.hip): new position of gathered token j of a
+// question = pos_offset (+ j unless is_static); cached keys carry no rotation, or (src_rotated)
+// the rotation of their stream position src_pos_offset + token index.
+struct RopeArgs {
+    double log2_base;
+    int64_t pos_offset, src_pos_offset;
+    int32_t is_static, src_rotated, interleaved;
+};
+hipError_t gather_rope_launch(const void* src_k, const void* src_v, int n_src_frames, const int32_t* idx,
+                              int n_questions, int k_slots, int n_f, int n_kv_heads, int d, int dtype,
+                              void* dst_k, void* dst_v, const RopeArgs& ra, hipStream_t stream);
+
 // Measurement probes (probe.hip).
 hipError_t launch_probe_copy(void* dst, const void* src, int64_t n_bytes, hipStream_t stream);
 hipError_t launch_probe_mfma(float* sink, int32_t n_workgroups, int32_t n_iters, hipStream_t stream);

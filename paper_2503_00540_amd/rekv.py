@@ -23,7 +23,7 @@ _DTYPES = {"f32": (REKV_F32, torch.float32), "bf16": (REKV_BF16, torch.bfloat16)
 # Every entry point include/rekv.h declares.
 SYMBOLS = ("rekv_create", "rekv_destroy", "rekv_last_error", "rekv_encode_chunk",
            "rekv_frame_keys", "rekv_retrieve_topk", "rekv_gather_kv", "rekv_qa_attention",
-           "rekv_decode_attention", "rekv_block_keys", "rekv_expand_blocks", "rekv_retrieve_external", "rekv_attention_indexed",
+           "rekv_decode_attention", "rekv_block_keys", "rekv_expand_blocks", "rekv_retrieve_external", "rekv_attention_indexed", "rekv_gather_kv_rope",
            "rekv_offload_kv", "rekv_offload_wait", "rekv_probe_copy", "rekv_probe_mfma")
 
 
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
     L.rekv_attention_indexed.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_int64,
                                          c_int32, c_void_p, c_void_p, c_int64, c_int32, c_int32, c_int32,
                                          c_void_p, c_void_p]
+    L.rekv_gather_kv_rope.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_int32, c_int32, c_void_p,
+                                      c_void_p, ctypes.c_double, c_int32, c_int32, c_int64, c_int32, c_int64, c_void_p]
     L.rekv_offload_kv.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32,
                                   c_void_p]
     L.rekv_offload_wait.argtypes = [c_void_p]
@@ -258,6 +260,27 @@ class Rekv:
         self._check(self._lib.rekv_gather_kv(
             self._h, ps[0], ps[1], host_mode if on_host else 0, nf, self._dev(idx, torch.int32, name="idx"), nq, k,
             self._dev(dst_k, name="dst_k"), self._dev(dst_v, name="dst_v"), _stream()))
+        return dst_k, dst_v
+
+    def gather_kv_rope(self, src_k, src_v, idx, n_src_frames: int | None = None, mode: str = "consecutive",
+                       pos_offset: int = 0, src_rotated: bool = False, src_pos_offset: int = 0,
+                       base: float = 10000.0, layout: str = "half"):
+        """rekv_gather_kv_rope: idx [n_questions, k] int32 on the device, source in HBM."""
+        kh = (self.n_kv_heads, self.head_dim)
+        nf = src_k.shape[0] // self.tokens_per_frame if n_src_frames is None else n_src_frames
+        if src_k.shape[0] < nf * self.tokens_per_frame or src_v.shape != src_k.shape:
+            raise ValueError("src_k / src_v are shorter than n_src_frames frames")
+        if idx.dim() != 2 or idx.dtype != torch.int32 or not idx.is_cuda or not idx.is_contiguous():
+            raise ValueError("idx must be a contiguous device tensor [n_questions, k] int32")
+        nq, k = idx.shape
+        shape = (nq, k * self.tokens_per_frame, *kh)
+        dst_k = torch.empty(shape, dtype=self.torch_dtype, device=idx.device)
+        dst_v = torch.empty(shape, dtype=self.torch_dtype, device=idx.device)
+        self._check(self._lib.rekv_gather_kv_rope(
+            self._h, self._dev(src_k, last=kh, name="src_k"), self._dev(src_v, last=kh, name="src_v"), nf,
+            idx.data_ptr(), nq, k, dst_k.data_ptr(), dst_v.data_ptr(), base,
+            {"half": 0, "interleaved": 1}[layout], {"consecutive": 0, "static": 1}[mode], pos_offset,
+            int(src_rotated), src_pos_offset, _stream()))
         return dst_k, dst_v
 
     def qa_attention(self, q, k_ret, v_ret, k_self, v_self, out=None):

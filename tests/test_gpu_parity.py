@@ -410,6 +410,43 @@ def test_gather_device_and_host_bit_exact():
                                        2, 5, gk.data_ptr(), gv.data_ptr(), None))
 
 
+@pytest.mark.parametrize("w,layout,mode,src_rotated", [
+    (W.C1, "half", "consecutive", False), (W.C1, "interleaved", "consecutive", True),
+    (W.C1, "half", "static", True), (W.C4, "half", "consecutive", True),
+    (W.C0.scaled(tokens_per_frame=7, name="C0r"), "half", "consecutive", True),
+    (W.C0.scaled(tokens_per_frame=7, name="C0r"), "interleaved", "static", False)],
+    ids=["7B-plain-cache", "7B-interleaved-rotated-cache", "7B-static", "72B", "f32", "f32-interleaved-static"])
+def test_gather_with_position_policy_matches_oracle(w, layout, mode, src_rotated):
+    """Keys turned to consecutive (or one static) position while they are gathered; the cache
+    holds plain keys or keys rotated at stream positions around 700,000 (an hour-long stream),
+    so the angles are large.  Values must be copied bit for bit; keys agree to one unit in the
+    last place of the storage type (the oracle is fp64, the result is rounded once)."""
+    w = w.scaled(n_frames=20)
+    r = Rekv.for_workload(w)
+    nf = w.tokens_per_frame
+    k, v = W.frames_k(w, 0, w.n_frames), W.frames_v(w, 0, w.n_frames)
+    src_off = 700_000
+    if src_rotated:
+        k = O.apply_rope(k, src_off + np.arange(k.shape[0]), layout=layout)
+        k = W.round_to_bf16(k) if w.dtype == "bf16" else k.astype(np.float32).astype(np.float64)
+    idx = np.array([[17, 3, 4, 9, -1], [0, 19, 18, -1, -1]], dtype=np.int32)
+    gk, gv = r.gather_kv_rope(dev(k, w), dev(v, w), torch.from_numpy(idx).to(DEV), mode=mode, pos_offset=35,
+                              src_rotated=src_rotated, src_pos_offset=src_off, layout=layout)
+    gk, gv = host(gk), host(gv)
+    for i in range(2):
+        frames = [f for f in idx[i] if f >= 0]
+        n = len(frames) * nf
+        rk, rv = O.gather_kv_rope(k, v, frames, nf, mode=mode, pos_offset=35, src_rotated=src_rotated,
+                                  src_pos_offset=src_off, layout=layout)
+        np.testing.assert_array_equal(gv[i, :n], rv)
+        ulp = 2.0 ** -8 if w.dtype == "bf16" else 2.0 ** -22
+        tol = ulp * np.abs(rk) + (1e-5 if w.dtype == "bf16" else 5e-5)
+        assert (np.abs(gk[i, :n] - rk) <= tol).all(), np.abs(gk[i, :n] - rk).max()
+        assert not gk[i, n:].any() and not gv[i, n:].any()               # -1 slots are zero-filled
+    with pytest.raises(RekvError):
+        r.gather_kv_rope(dev(k, w), dev(v, w), torch.from_numpy(idx).to(DEV), base=1.0)
+
+
 # ----------------------------------------------------------------------------------------
 # QA attention, Eq. 3
 # ----------------------------------------------------------------------------------------
