@@ -126,18 +126,198 @@ __device__ inline float transpose_reduce(float (&v)[N], int lane) {
     return v[0];
 }
 
-template <int FR, int QBT>
+// ---------------------------------------------------------------------------------------
+// Exact top-k of one question's scores.  Scores become order-preserving 32-bit keys; a
+// 4-pass radix select (8 bits per pass, histogram in LDS) finds the k-th largest key T;
+// then one ordered pass over the frames writes, in ascending frame index, every frame with
+// key > T and the first (k - count) frames with key == T - the lower index wins ties.
+// One block per question.
+// ---------------------------------------------------------------------------------------
+constexpr int TOPK_THREADS = 256;
+
+__device__ inline uint32_t order_key(float s) {
+    uint32_t u = __float_as_uint(s);
+    if (u == 0x80000000u) u = 0u;          // -0 and +0 are the same score
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// exclusive scan over the block of two counts per thread, packed into one 64-bit value
+// (high word, low word); returns this thread's prefix and the block total through `total`
+__device__ inline uint64_t block_excl_scan(uint64_t v, uint64_t* wave_tot, uint64_t& total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint64_t inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint64_t n = __shfl_up(inc, o);
+        if (lane >= o) inc += n;
+    }
+    __syncthreads();                       // wave_tot may still be read from the last call
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    uint64_t before = 0;
+    total = 0;
+#pragma unroll
+    for (int w = 0; w < TOPK_THREADS / 64; ++w) {
+        const uint64_t t = wave_tot[w];
+        if (w < wave) before += t;
+        total += t;
+    }
+    return before + inc - v;
+}
+
+// The whole block works on one question: s its n_frames scores, out its k index slots, n_sel_q
+// its count (may be NULL).
+__device__ inline void topk_block(const float* s, int n_frames, int k, int32_t* out, int32_t* n_sel_q) {
+    // Scores of one question cluster in a few exponent bins, so a single histogram would serialise
+    // its LDS atomics on one address: threads spread over NSUB copies, and each thread first adds
+    // up runs of equal bins among its own keys.
+    // The kernel runs once per question on cold instruction caches, so its loops stay rolled: the
+    // code is a few hundred instructions, not thousands.
+    constexpr int NSUB = 8;
+    constexpr int SPAN = 16;               // consecutive frames a thread owns in the ordered sweep
+    __shared__ int hist[NSUB][256];
+    __shared__ uint32_t keys[SPAN * TOPK_THREADS];
+    __shared__ uint64_t wave_tot[TOPK_THREADS / 64];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int sh_need;
+    const int tid = threadIdx.x;
+
+    if (k >= n_frames) {                   // everything is selected
+        for (int f = tid; f < k; f += TOPK_THREADS) out[f] = f < n_frames ? f : -1;
+        if (tid == 0 && n_sel_q) *n_sel_q = n_frames;
+        return;
+    }
+
+    // Up to 4096 frames the keys live in LDS (frame f at [f % SPAN][f / SPAN], which both the
+    // strided and the owner-contiguous access below reach without bank conflicts), so the scores
+    // cross the memory system once instead of once per pass.
+    const bool resident = n_frames <= TOPK_THREADS * SPAN;
+    if (resident) {
+#pragma unroll 1
+        for (int f = tid; f < n_frames; f += TOPK_THREADS)
+            keys[(f % SPAN) * TOPK_THREADS + f / SPAN] = order_key(s[f]);
+        __syncthreads();
+    }
+    auto key_at = [&](int f) -> uint32_t {
+        return resident ? keys[(f % SPAN) * TOPK_THREADS + f / SPAN] : order_key(s[f]);
+    };
+
+    uint32_t prefix = 0;                   // high bits of T found so far
+    int need = k;                          // rank of T among keys matching the prefix
+#pragma unroll 1
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+#pragma unroll 1
+        for (int sub = 0; sub < NSUB; ++sub) hist[sub][tid] = 0;    // TOPK_THREADS == 256 bins
+        __syncthreads();
+        const uint32_t hi_mask = pass ? (0xFFFFFFFFu << (shift + 8)) : 0u;
+        int* my_hist = hist[tid % NSUB];
+        int run_bin = -1, run_len = 0;
+#pragma unroll 1
+        for (int f = tid; f < n_frames; f += TOPK_THREADS) {
+            const uint32_t key = key_at(f);
+            if ((key & hi_mask) != prefix) continue;
+            const int bin = (int)((key >> shift) & 255u);
+            if (bin == run_bin) {
+                ++run_len;
+            } else {
+                if (run_len) atomicAdd(&my_hist[run_bin], run_len);
+                run_bin = bin;
+                run_len = 1;
+            }
+        }
+        if (run_len) atomicAdd(&my_hist[run_bin], run_len);
+        __syncthreads();
+        // bin b is chosen iff (#keys in bins above b) < need <= (#keys in bins >= b)
+        int mine = 0;
+#pragma unroll 1
+        for (int sub = 0; sub < NSUB; ++sub) mine += hist[sub][tid];
+        uint64_t total;
+        const int below = (int)block_excl_scan((uint64_t)mine, wave_tot, total);   // keys in bins < tid
+        const int above = (int)total - below - mine;
+        if (above < need && need <= above + mine) {
+            sh_prefix = prefix | ((uint32_t)tid << shift);
+            sh_need = need - above;
+        }
+        __syncthreads();
+        prefix = sh_prefix;
+        need = sh_need;
+        __syncthreads();
+    }
+    const uint32_t T = prefix;             // the k-th largest key; `need` of its copies are taken
+
+    // ordered sweep: a thread owns SPAN consecutive frames, so one block scan orders 4096 frames
+    int base_gt = 0, base_eq = 0;          // frames above T / equal to T before this sweep
+#pragma unroll 1
+    for (int f0 = 0; f0 < n_frames; f0 += TOPK_THREADS * SPAN) {
+        const int fa = f0 + tid * SPAN;
+        uint32_t gt_mask = 0, eq_mask = 0;
+#pragma unroll 1
+        for (int i = 0; i < SPAN; ++i)
+            if (fa + i < n_frames) {
+                const uint32_t key = key_at(fa + i);
+                gt_mask |= (uint32_t)(key > T) << i;
+                eq_mask |= (uint32_t)(key == T) << i;
+            }
+        uint64_t tot;
+        const uint64_t pre = block_excl_scan(((uint64_t)__popc(gt_mask) << 32) | (uint64_t)__popc(eq_mask),
+                                             wave_tot, tot);
+        int n_gt = base_gt + (int)(pre >> 32), n_eq = base_eq + (int)(pre & 0xFFFFFFFFu);
+#pragma unroll 1
+        for (int i = 0; i < SPAN; ++i) {
+            const bool gt = (gt_mask >> i) & 1, eq = (eq_mask >> i) & 1;
+            if (gt || (eq && n_eq < need)) out[n_gt + (n_eq < need ? n_eq : need)] = fa + i;
+            n_gt += gt;
+            n_eq += eq;
+        }
+        base_gt += (int)(tot >> 32);
+        base_eq += (int)(tot & 0xFFFFFFFFu);
+    }
+    if (tid == 0 && n_sel_q) *n_sel_q = k;
+}
+
+__global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float* __restrict__ scores,
+                                                            int n_frames, int k,
+                                                            int32_t* __restrict__ idx,
+                                                            int32_t* __restrict__ n_sel) {
+    const int64_t qi = blockIdx.x;
+    topk_block(scores + qi * n_frames, n_frames, k, idx + qi * k, n_sel ? n_sel + qi : nullptr);
+}
+
+
+// For the single-question score kernel: the per-head token means it averages into the question
+// vector itself (NULL: q_vec is given), which saves the group-mean launch.
+struct QuestionHeads {
+    const float* q_heads;   // [n_questions, Hq * D] or NULL
+    int hq, hkv, d;
+};
+
+template <int FR, int QBT, bool POOL>
 __global__ __launch_bounds__(SCORE_WAVES * 64) void score_kernel(
     const float* __restrict__ frame_keys, int64_t fk_stride, int n_frames, int d_prime,
-    const float* __restrict__ q_vec, int n_questions, float inv_tau, float* __restrict__ scores) {
+    const float* __restrict__ q_vec, int n_questions, float inv_tau, float* __restrict__ scores, QuestionHeads ft) {
+    static_assert(!POOL || QBT == 1, "in-kernel group mean serves one question per block");
     static_assert(FR * QBT <= 64 && (FR & (FR - 1)) == 0 && (QBT & (QBT - 1)) == 0, "butterfly sizes");
     extern __shared__ float qs[];            // [QBT][d_prime] then [QBT] squared norms
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int q0 = blockIdx.y * QBT;
     const int nq_here = n_questions - q0 < QBT ? n_questions - q0 : QBT;
     float* qn = qs + QBT * d_prime;
-    for (int i = threadIdx.x; i < QBT * d_prime; i += blockDim.x)     // absent questions stay zero
-        qs[i] = i < nq_here * d_prime ? q_vec[(int64_t)q0 * d_prime + i] : 0.f;
+    if (POOL && ft.q_heads) {
+        // the question vector: mean of the G query heads of each KV group (same order of sums as
+        // group_mean_kernel)
+        const int g_sz = ft.hq / ft.hkv;
+        for (int i = threadIdx.x; i < d_prime; i += blockDim.x) {
+            const int g = i / ft.d, dd = i - g * ft.d;
+            const float* src = ft.q_heads + ((int64_t)q0 * ft.hq + g * g_sz) * ft.d + dd;
+            float acc = 0.f;
+            for (int j = 0; j < g_sz; ++j) acc += src[j * ft.d];
+            qs[i] = acc / (float)g_sz;
+        }
+    } else {
+        for (int i = threadIdx.x; i < QBT * d_prime; i += blockDim.x)     // absent questions stay zero
+            qs[i] = i < nq_here * d_prime ? q_vec[(int64_t)q0 * d_prime + i] : 0.f;
+    }
     __syncthreads();
     for (int w = wave; w < QBT; w += SCORE_WAVES) {
         float s = 0.f;
@@ -185,122 +365,6 @@ __global__ __launch_bounds__(SCORE_WAVES * 64) void score_kernel(
             scores[(int64_t)(q0 + w) * n_frames + f0 + fr] = den > 0.f ? dsum / den * inv_tau : 0.f;
         }
     }
-}
-
-// ---------------------------------------------------------------------------------------
-// Exact top-k of one question's scores.  Scores become order-preserving 32-bit keys; a
-// 4-pass radix select (8 bits per pass, histogram in LDS) finds the k-th largest key T;
-// then one ordered pass over the frames writes, in ascending frame index, every frame with
-// key > T and the first (k - count) frames with key == T - the lower index wins ties.
-// One block per question.
-// ---------------------------------------------------------------------------------------
-constexpr int TOPK_THREADS = 256;
-
-__device__ inline uint32_t order_key(float s) {
-    uint32_t u = __float_as_uint(s);
-    if (u == 0x80000000u) u = 0u;          // -0 and +0 are the same score
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-// exclusive scan over the block of two counts per thread, packed into one 64-bit value
-// (high word, low word); returns this thread's prefix and the block total through `total`
-__device__ inline uint64_t block_excl_scan(uint64_t v, uint64_t* wave_tot, uint64_t& total) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint64_t inc = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint64_t n = __shfl_up(inc, o);
-        if (lane >= o) inc += n;
-    }
-    __syncthreads();                       // wave_tot may still be read from the last call
-    if (lane == 63) wave_tot[wave] = inc;
-    __syncthreads();
-    uint64_t before = 0;
-    total = 0;
-#pragma unroll
-    for (int w = 0; w < TOPK_THREADS / 64; ++w) {
-        const uint64_t t = wave_tot[w];
-        if (w < wave) before += t;
-        total += t;
-    }
-    return before + inc - v;
-}
-
-__global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float* __restrict__ scores,
-                                                            int n_frames, int k,
-                                                            int32_t* __restrict__ idx,
-                                                            int32_t* __restrict__ n_sel) {
-    __shared__ int hist[256];
-    __shared__ uint64_t wave_tot[TOPK_THREADS / 64];
-    __shared__ uint32_t sh_prefix;
-    __shared__ int sh_need;
-    const int64_t qi = blockIdx.x;
-    const float* s = scores + qi * n_frames;
-    int32_t* out = idx + qi * k;
-    const int tid = threadIdx.x;
-
-    if (k >= n_frames) {                   // everything is selected
-        for (int f = tid; f < k; f += TOPK_THREADS) out[f] = f < n_frames ? f : -1;
-        if (tid == 0 && n_sel) n_sel[qi] = n_frames;
-        return;
-    }
-
-    uint32_t prefix = 0;                   // high bits of T found so far
-    int need = k;                          // rank of T among keys matching the prefix
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        hist[tid] = 0;                     // TOPK_THREADS == 256 bins
-        __syncthreads();
-        const uint32_t hi_mask = pass ? (0xFFFFFFFFu << (shift + 8)) : 0u;
-        for (int f = tid; f < n_frames; f += TOPK_THREADS) {
-            const uint32_t key = order_key(s[f]);
-            if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1);
-        }
-        __syncthreads();
-        // bin b is chosen iff (#keys in bins above b) < need <= (#keys in bins >= b)
-        const int mine = hist[tid];
-        uint64_t total;
-        const int below = (int)block_excl_scan((uint64_t)mine, wave_tot, total);   // keys in bins < tid
-        const int above = (int)total - below - mine;
-        if (above < need && need <= above + mine) {
-            sh_prefix = prefix | ((uint32_t)tid << shift);
-            sh_need = need - above;
-        }
-        __syncthreads();
-        prefix = sh_prefix;
-        need = sh_need;
-        __syncthreads();
-    }
-    const uint32_t T = prefix;             // the k-th largest key; `need` of its copies are taken
-
-    // ordered sweep: a thread owns SPAN consecutive frames, so one block scan orders 4096 frames
-    constexpr int SPAN = 16;
-    int base_gt = 0, base_eq = 0;          // frames above T / equal to T before this sweep
-    for (int f0 = 0; f0 < n_frames; f0 += TOPK_THREADS * SPAN) {
-        const int fa = f0 + tid * SPAN;
-        uint32_t gt_mask = 0, eq_mask = 0;
-#pragma unroll
-        for (int i = 0; i < SPAN; ++i)
-            if (fa + i < n_frames) {
-                const uint32_t key = order_key(s[fa + i]);
-                gt_mask |= (uint32_t)(key > T) << i;
-                eq_mask |= (uint32_t)(key == T) << i;
-            }
-        uint64_t tot;
-        const uint64_t pre = block_excl_scan(((uint64_t)__popc(gt_mask) << 32) | (uint64_t)__popc(eq_mask),
-                                             wave_tot, tot);
-        int n_gt = base_gt + (int)(pre >> 32), n_eq = base_eq + (int)(pre & 0xFFFFFFFFu);
-#pragma unroll
-        for (int i = 0; i < SPAN; ++i) {
-            const bool gt = (gt_mask >> i) & 1, eq = (eq_mask >> i) & 1;
-            if (gt || (eq && n_eq < need)) out[n_gt + (n_eq < need ? n_eq : need)] = fa + i;
-            n_gt += gt;
-            n_eq += eq;
-        }
-        base_gt += (int)(tot >> 32);
-        base_eq += (int)(tot & 0xFFFFFFFFu);
-    }
-    if (tid == 0 && n_sel) n_sel[qi] = k;
 }
 
 }  // namespace
@@ -375,38 +439,42 @@ hipError_t expand_blocks_launch(const int32_t* block_idx, int n_questions, int k
 
 hipError_t retrieve_launch(const RetrieveArgs& a, hipStream_t stream) {
     const int d_prime = a.dim > 0 ? a.dim : a.n_kv_heads * a.head_dim;
+    // Many questions on one table: 8 frames x 8 questions per wavefront (if 8 question vectors
+    // fit 48 KB of LDS), after a group-mean launch.  Otherwise one question per block row, 4 frames
+    // per wavefront, and the kernel averages the query heads itself.
+    const bool batched = a.frame_keys_stride == 0 && a.n_questions > 1 &&
+                         (size_t)8 * (d_prime + 1) * sizeof(float) <= 48 * 1024;
     const float* q_vec = a.q_vec_given;
     hipError_t e = hipSuccess;
     if (!q_vec) {
-        // token mean per query head: [n_questions, Hq * D] fp32, then the group mean: [n_questions, D']
+        // token mean per query head: [n_questions, Hq * D] fp32
         e = frame_keys_launch(a.q_question, a.n_questions, a.n_q_tokens, a.n_q_heads * a.head_dim,
                               a.dtype, a.q_heads, stream);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(group_mean_kernel, dim3((unsigned)a.n_questions, (unsigned)((d_prime + 255) / 256)),
-                           dim3(256), 0, stream, a.q_heads, a.n_q_heads, a.n_kv_heads, a.head_dim, a.q_vec);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        q_vec = a.q_vec;
+        if (batched) {                 // then the group mean: [n_questions, D']
+            hipLaunchKernelGGL(group_mean_kernel, dim3((unsigned)a.n_questions, (unsigned)((d_prime + 255) / 256)),
+                               dim3(256), 0, stream, a.q_heads, a.n_q_heads, a.n_kv_heads, a.head_dim, a.q_vec);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            q_vec = a.q_vec;
+        }
     }
-
-    // Many questions on one table: 8 frames x 8 questions per wavefront (if 8 question vectors
-    // fit 48 KB of LDS).  One question per table: 4 frames per wavefront.
-    const bool batched = a.frame_keys_stride == 0 && a.n_questions > 1 &&
-                         (size_t)8 * (d_prime + 1) * sizeof(float) <= 48 * 1024;
     const int fr = batched ? 8 : 4, qbt = batched ? 8 : 1;
     int fblocks = (a.n_frames + SCORE_WAVES * fr - 1) / (SCORE_WAVES * fr);
     if (fblocks > 4096) fblocks = 4096;
     dim3 sg((unsigned)fblocks, (unsigned)((a.n_questions + qbt - 1) / qbt));
     const size_t lds = (size_t)qbt * (d_prime + 1) * sizeof(float);
+    QuestionHeads ft;
+    ft.q_heads = q_vec ? nullptr : a.q_heads;
+    ft.hq = a.n_q_heads; ft.hkv = a.n_kv_heads; ft.d = a.head_dim;
     if (batched)
-        hipLaunchKernelGGL((score_kernel<8, 8>), sg, dim3(SCORE_WAVES * 64), lds, stream, a.frame_keys,
-                           a.frame_keys_stride, a.n_frames, d_prime, q_vec, a.n_questions, a.inv_tau, a.scores);
+        hipLaunchKernelGGL((score_kernel<8, 8, false>), sg, dim3(SCORE_WAVES * 64), lds, stream, a.frame_keys,
+                           a.frame_keys_stride, a.n_frames, d_prime, q_vec, a.n_questions, a.inv_tau, a.scores, ft);
     else
-        hipLaunchKernelGGL((score_kernel<4, 1>), sg, dim3(SCORE_WAVES * 64), lds, stream, a.frame_keys,
-                           a.frame_keys_stride, a.n_frames, d_prime, q_vec, a.n_questions, a.inv_tau, a.scores);
+        hipLaunchKernelGGL((score_kernel<4, 1, true>), sg, dim3(SCORE_WAVES * 64), lds, stream, a.frame_keys,
+                           a.frame_keys_stride, a.n_frames, d_prime, q_vec, a.n_questions, a.inv_tau, a.scores, ft);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-
     hipLaunchKernelGGL(topk_kernel, dim3((unsigned)a.n_questions), dim3(TOPK_THREADS), 0, stream,
                        a.scores, a.n_frames, a.k, a.idx, a.n_sel);
     return hipGetLastError();
