@@ -176,7 +176,7 @@ __device__ inline void topk_block(const float* s, int n_frames, int k, int32_t* 
     constexpr int NSUB = 8;
     constexpr int SPAN = 16;               // consecutive frames a thread owns in the ordered sweep
     __shared__ int hist[NSUB][256];
-    __shared__ uint32_t keys[SPAN * TOPK_THREADS];
+    __shared__ __attribute__((aligned(16))) uint32_t keys[SPAN * TOPK_THREADS];
     __shared__ uint64_t wave_tot[TOPK_THREADS / 64];
     __shared__ uint32_t sh_prefix;
     __shared__ int sh_need;
@@ -186,6 +186,36 @@ __device__ inline void topk_block(const float* s, int n_frames, int k, int32_t* 
         for (int f = tid; f < k; f += TOPK_THREADS) out[f] = f < n_frames ? f : -1;
         if (tid == 0 && n_sel_q) *n_sel_q = n_frames;
         return;
+    }
+
+    // Up to 256 frames (one per thread): count, for every frame, the frames with a higher key - all
+    // keys in LDS, read as broadcasts - and take those with fewer than k above them.  That is the
+    // answer unless equal keys straddle the cut, which shows as more than k taken; then (rarely)
+    // the radix select below decides.
+    if (n_frames <= TOPK_THREADS) {
+        const int n4 = (n_frames + 3) >> 2;        // keys are read four at a time; key 0 pads the tail
+        for (int f = tid; f < n4 * 4; f += TOPK_THREADS) keys[f] = f < n_frames ? order_key(s[f]) : 0u;
+        __syncthreads();
+        const uint4* keys4 = reinterpret_cast<const uint4*>(keys);
+        const uint32_t mine = tid < n_frames ? keys[tid] : 0xFFFFFFFFu;
+        int above = 0;                             // padding keys (0) are above nothing
+#pragma unroll 8
+        for (int j4 = 0; j4 < n4; ++j4) {
+            const uint4 o = keys4[j4];
+            above += o.x > mine;
+            above += o.y > mine;
+            above += o.z > mine;
+            above += o.w > mine;
+        }
+        const bool take = tid < n_frames && above < k;
+        uint64_t tot;
+        const uint64_t pre = block_excl_scan((uint64_t)take, wave_tot, tot);
+        if ((int)tot == k) {                       // uniform over the block
+            if (take) out[(int)pre] = tid;
+            if (tid == 0 && n_sel_q) *n_sel_q = k;
+            return;
+        }
+        __syncthreads();                           // keys[] is laid out anew below
     }
 
     // Up to 4096 frames the keys live in LDS (frame f at [f % SPAN][f / SPAN], which both the

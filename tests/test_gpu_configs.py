@@ -169,3 +169,50 @@ def test_c4_many_concurrent_questions():
         assert host(gv)[i].tobytes() == rv.astype(np.float64).tobytes()
         ref = O.qa_attention(qs[i][0], rk, rv, qs[i][1], qs[i][2])
         assert np.abs(host(o)[i] - ref).max() < TOL, i
+
+
+def test_retrieval_and_qa_replay_from_a_hip_graph():
+    """The question-time part of the path (retrieval, gather, QA attention; and the variant that
+    reads the retrieved frames in place) captured into a HIP graph: every replay, with eager work
+    and synchronisations of the program in between, must give the eager result bit for bit.  The
+    calls launch kernels only (no memset or copy nodes) once the context's workspace exists."""
+    w = W.C1.scaled(n_frames=64)
+    r = Rekv.for_workload(w)
+    F = w.n_frames
+    g = torch.Generator(device=DEV).manual_seed(11)
+    mk = lambda *s: torch.randn(*s, device=DEV, generator=g).to(torch.bfloat16)
+    k, v = mk(F * w.tokens_per_frame, w.n_kv_heads, w.head_dim), mk(F * w.tokens_per_frame, w.n_kv_heads, w.head_dim)
+    qq = mk(2, w.n_q_tokens, w.n_q_heads, w.head_dim)
+    qk, qv = mk(2, w.n_q_tokens, w.n_kv_heads, w.head_dim), mk(2, w.n_q_tokens, w.n_kv_heads, w.head_dim)
+    fk = r.frame_keys(k, F)
+
+    def gathered():
+        idx, _, _ = r.retrieve_topk(fk, F, qq, w.top_k)
+        gk, gv = r.gather_kv(k, v, idx, n_src_frames=F)
+        return r.qa_attention(qq, gk, gv, qk, qv), idx
+
+    def in_place():
+        idx, _, _ = r.retrieve_topk(fk, F, qq, w.top_k)
+        return r.attention_indexed(qq, k, v, idx, w.top_k, qk, qv, w.n_q_tokens, n_src_frames=F), idx
+
+    for fn in (gathered, in_place):
+        ref, ref_idx = fn()                              # eager; also grows the workspace before capture
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            out, idx = fn()
+        for _ in range(4):
+            out.zero_()
+            idx.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, ref) and torch.equal(idx, ref_idx)
+            scratch = r.frame_keys(k, F)                 # eager library work between replays
+            assert torch.equal(scratch, fk)

@@ -351,14 +351,17 @@ def test_topk_ties_and_degenerate_sizes():
     k[40:] = np.tile(k[:40], (15, 1, 1))[: len(k) - 40]     # frames repeat with period 20: exact ties
     fk = r.frame_keys(dev(k, w), w.n_frames)
     qq = W.question_qkv(w)[0]
-    for kk in (1, 2, 15, 16, 17, 64, 299, 300, 301, 500):
-        idx, n_sel, scores = r.retrieve_topk(fk, w.n_frames, dev(qq, w)[None], kk, want_scores=True)
-        s = host(scores)[0]
-        assert len(np.unique(s)) <= 21
-        ref = O.topk_frames(s, kk)
-        got = idx[0].cpu().numpy()
-        np.testing.assert_array_equal(got[: len(ref)], ref)
-        assert (got[len(ref):] == -1).all() and int(n_sel[0]) == min(kk, 300)
+    # 300 frames go through the radix select; 200 and 64 through the one-pass count for small
+    # tables, where a tie group straddling the cut (k = 15, 17, ...) must hand over to the radix select
+    for n_vis in (300, 200, 64):
+        for kk in (1, 2, 15, 16, 17, 64, 199, 200, 299, 300, 301, 500):
+            idx, n_sel, scores = r.retrieve_topk(fk, n_vis, dev(qq, w)[None], kk, want_scores=True)
+            s = host(scores)[0]
+            assert len(np.unique(s)) <= 21
+            ref = O.topk_frames(s, kk)
+            got = idx[0].cpu().numpy()
+            np.testing.assert_array_equal(got[: len(ref)], ref)
+            assert (got[len(ref):] == -1).all() and int(n_sel[0]) == min(kk, n_vis)
     # zero keys and a zero question score 0 everywhere: the first k frames win
     z = torch.zeros_like(fk)
     idx, _, scores = r.retrieve_topk(z, 300, dev(qq, w)[None], 5, want_scores=True)
