@@ -130,6 +130,38 @@ def test_encode_matches_oracle(case):
         assert err < TOL[w.dtype], ("single", c, err)
 
 
+def _random_encode_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        hkv = int(rng.choice([1, 2, 4]))
+        g = int(rng.choice([1, 2, 3, 5, 7, 8]))
+        cases.append(dict(dtype=str(rng.choice(["bf16", "bf16", "f32"])), hkv=hkv, hq=hkv * g,
+                          d=int(rng.choice([64, 128])), nf=int(rng.integers(1, 71)),
+                          chunk_frames=int(rng.integers(1, 4)), n_chunks=int(rng.integers(1, 5)),
+                          first_chunk=int(rng.integers(0, 4)), l_l=int(rng.choice([0, 1, 31, 32, 33, 100, 257, 10 ** 6])),
+                          seed=i))
+    return cases
+
+
+@pytest.mark.parametrize("c", _random_encode_cases(24, 2024), ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
+def test_encode_random_shapes(c):
+    """Seeded sweep over head layouts, head sizes, frame sizes that are no multiple of anything,
+    window lengths around the 32-key tile, calls that start in mid-stream and hold several chunks;
+    every output row is compared."""
+    w = W.C1.scaled(dtype=c["dtype"], n_q_heads=c["hq"], n_kv_heads=c["hkv"], head_dim=c["d"],
+                    tokens_per_frame=c["nf"], chunk_frames=c["chunk_frames"],
+                    n_frames=(c["first_chunk"] + c["n_chunks"]) * c["chunk_frames"], name=f"rnd{c['seed']}")
+    q, k, v = W.frames_q(w, 0, w.n_frames), W.frames_k(w, 0, w.n_frames), W.frames_v(w, 0, w.n_frames)
+    r = Rekv.for_workload(w)
+    t0 = c["first_chunk"] * w.l_x
+    sl = slice(t0, t0 + c["n_chunks"] * w.l_x)
+    out = host(r.encode_chunk(dev(q[sl], w), dev(k, w), dev(v, w), t0, w.l_x, c["n_chunks"], c["l_l"]))
+    ref = O.encode_chunks(q[sl], k, v, t0, w.l_x, c["n_chunks"], c["l_l"])
+    err = np.abs(out - ref).max()
+    assert err < TOL[w.dtype], err
+
+
 def test_encode_single_token_chunks_and_custom_scale():
     """l_x = 1 (a chunk is one token) and a caller-given softmax scale."""
     w = W.C1.scaled(n_frames=3)
