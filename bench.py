@@ -231,6 +231,7 @@ def main() -> None:
         hv = torch.empty(d["v"][0].shape, dtype=tdt, pin_memory=True)
 
     names = ["encode", "frame_keys", "offload_issue", "offload_wait", "retrieve", "gather", "qa"]
+    N_SEG = 8
 
     def one_step(log=None):
         def rec(name):
@@ -239,13 +240,25 @@ def main() -> None:
                 e.record()
                 log.append((name, e))
         for layer in range(L):
+            if w.kv_on_host:
+                # the stream is encoded in N_SEG launches; each segment's KV leaves HBM on the side
+                # stream (copy engine) while the next segment is being encoded
+                q_l, k_l, v_l = d["q"][layer % len(d["q"])], d["k"][layer], d["v"][layer]
+                for sgm in range(N_SEG):
+                    c0, c1 = sgm * n_chunks // N_SEG, (sgm + 1) * n_chunks // N_SEG
+                    rec("encode")
+                    r.encode_chunk(q_l[c0 * w.l_x:c1 * w.l_x], k_l, v_l, c0 * w.l_x, w.l_x, c1 - c0, w.l_l,
+                                   out=out[c0 * w.l_x:c1 * w.l_x])
+                    rec("frame_keys")
+                    f0, f1 = c0 * w.chunk_frames, c1 * w.chunk_frames
+                    r.frame_keys(k_l[f0 * nf:f1 * nf], f1 - f0, out=fk[layer][f0:f1])
+                    rec("offload_issue")
+                    r.offload_kv(k_l, v_l, hk, hv, f0, f1 - f0)
+                continue
             rec("encode")
             r.encode_chunk(d["q"][layer % len(d["q"])], d["k"][layer], d["v"][layer], 0, w.l_x, n_chunks, w.l_l, out=out)
             rec("frame_keys")
             r.frame_keys(d["k"][layer], F, out=fk[layer])
-            if w.kv_on_host:           # the encoded KV leaves HBM on the side stream while the path goes on
-                rec("offload_issue")
-                r.offload_kv(d["k"][layer], d["v"][layer], hk, hv, 0, F)
         if w.kv_on_host:               # the question arrives once the stream's KV has left HBM
             rec("offload_wait")
             r.offload_wait()
@@ -352,7 +365,9 @@ def main() -> None:
         bound, peak = "mfma", PEAK_BF16_TFLOPS
     else:
         bound, peak = "alu", PEAK_FP32_VALU_TFLOPS
-    enc_launch_ms = ms["encode"] / L
+    n_launch = N_SEG if w.kv_on_host else 1                # encode launches per layer
+    fl /= n_launch
+    enc_launch_ms = ms["encode"] / (L * n_launch)
     achieved = fl / (enc_launch_ms * 1e-3) / 1e12
     es = 2 if w.dtype == "bf16" else 4
     gather_bytes = 2 * L * nq * w.top_k * nf * d_prime * es          # K and V, read once (and written once)
@@ -366,9 +381,9 @@ def main() -> None:
                                f"Hq/Hkv/D {w.n_q_heads}/{w.n_kv_heads}/{w.head_dim}, chunk {w.l_x} tokens, "
                                f"window {w.l_l} tokens, {nq} question(s) of {w.n_q_tokens} tokens, "
                                f"top-k {w.top_k}, KV {'offloaded to pinned host memory' if w.kv_on_host else 'in HBM'}; "
-                               f"a step = per layer: encode all {n_chunks} chunks in one launch + frame vectors"
+                               f"a step = per layer: encode all {n_chunks} chunks in {N_SEG if w.kv_on_host else 1} launch(es) + frame vectors"
                                f"{' + KV offload' if w.kv_on_host else ''}; then retrieval + gather + QA attention",
-                   "n_chunks_per_launch": n_chunks},
+                   "n_chunks_per_launch": n_chunks // (N_SEG if w.kv_on_host else 1)},
         "roofline": {"bound": bound, "kernel": "attn_bf16_kernel<D, true> (rekv_encode_chunk)" if w.dtype == "bf16"
                      else "attn_f32_kernel (rekv_encode_chunk)",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
