@@ -288,6 +288,15 @@ def main() -> None:
     for log in logs:
         for (name, e0), (_, e1) in zip(log[:-1], log[1:]):
             ms[name] += e0.elapsed_time(e1) / steps
+    # per-step latency from "question available" to "QA output ready" (retrieve + gather + QA)
+    lat = []
+    for log in logs:
+        t = 0.0
+        for (name, e0), (_, e1) in zip(log[:-1], log[1:]):
+            if name in ("retrieve", "gather", "qa"):
+                t += e0.elapsed_time(e1)
+        lat.append(t)
+    lat.sort()
     ms_per_step = elapsed / steps * 1e3
     n_tokens = L * w.n_tokens
     tokens_per_s = n_tokens / (elapsed / steps)
@@ -391,6 +400,7 @@ def main() -> None:
                      "algorithmic_flop_per_launch": fl, "avg_launch_ms": enc_launch_ms},
         "kernel_ms": ms,
         "retrieval_qa_latency_ms": ms["retrieve"] + ms["gather"] + ms["qa"],
+        "retrieval_qa_latency_ms_median": lat[len(lat) // 2], "retrieval_qa_latency_ms_min": lat[0],
         "encode_only_tokens_per_s": n_tokens / (ms["encode"] * 1e-3),
         "streaming_tokens_per_s": w.n_tokens / streaming_s if streaming_s else None,
         "hbm": {("gather_host_link_GBs" if w.kv_on_host else "gather_read_plus_write_GBs"):
