@@ -59,11 +59,11 @@ __global__ __launch_bounds__(256) void frame_keys_kernel(const void* __restrict_
         for (; j + n_rg * (U - 1) < n_f; j += n_rg * U) {
             u32x4 w[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) w[u] = *reinterpret_cast<const u32x4*>(base + (j + n_rg * u) * pitch);
+            for (int u = 0; u < U; ++u) w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + (j + n_rg * u) * pitch));
 #pragma unroll
             for (int u = 0; u < U; ++u) add(w[u]);
         }
-        for (; j < n_f; j += n_rg) add(*reinterpret_cast<const u32x4*>(base + j * pitch));
+        for (; j < n_f; j += n_rg) add(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + j * pitch)));
     }
 #pragma unroll
     for (int i = 0; i < VEC; ++i) red[(rg * lpr + cl) * VEC + i] = acc[i];
