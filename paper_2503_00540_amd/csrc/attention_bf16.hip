@@ -94,9 +94,16 @@ __device__ inline void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // 
 // wait-count bookkeeping: with more than a handful of such loads in a loop it would drain
 // all of them before any LDS read.  Ordering is explicit instead (step_barrier).
 // The source address is a wave-uniform base plus a 32-bit per-lane byte offset.
+// NT marks the load non-temporal: for keys and values that no other workgroup will read again
+// (a decode step), so they stream past the caches instead of displacing what is reused.
+template <bool NT>
 __device__ inline void dma16(const void* base, uint32_t lane_off, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 ::"v"(lane_off), "s"(base), "s"(__builtin_amdgcn_readfirstlane(lds_addr)) : "memory", "m0");
+    if (NT)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                     ::"v"(lane_off), "s"(base), "s"(__builtin_amdgcn_readfirstlane(lds_addr)) : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     ::"v"(lane_off), "s"(base), "s"(__builtin_amdgcn_readfirstlane(lds_addr)) : "memory", "m0");
 }
 __device__ inline uint32_t lds_addr_of(const void* p) {
     return (uint32_t)(uintptr_t)(LDS_AS const void*)p;
@@ -129,9 +136,11 @@ using IC = std::integral_constant<int, I>;
 // INDEXED: segment A is read from the KV arena through a frame index list (no gathered copy).
 constexpr int MAX_INDEXED_FRAMES = 1024;   // index entries staged in LDS per workgroup
 
-template <int D, bool ENCODE, bool INDEXED>
+// STREAM: every K/V tile is read by this workgroup only (one row block per item), see dma16.
+template <int D, bool ENCODE, bool INDEXED, bool STREAM>
 __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     static_assert(!(ENCODE && INDEXED), "the encode window is contiguous");
+    static_assert(!(STREAM && (ENCODE || INDEXED)), "streaming loads serve the plain QA / decode layout");
     typedef Cfg<D> C;
     __shared__ int32_t frame_of_slot[INDEXED ? MAX_INDEXED_FRAMES : 1];
     // K stages 0..3, then V stages 0..3; one array so that every stage is a constant offset
@@ -245,13 +254,13 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
             if (within < 0) { --slot; within += p.n_f; }
             if (within >= p.n_f) { ++slot; within -= p.n_f; }
             const uint32_t src_row = (uint32_t)(frame_of_slot[slot] * p.n_f + within);
-            dma16(arena, src_row * row_stride_b + dma_coff[j], dma_lds + stage_b + j * 1024u);
+            dma16<STREAM>(arena, src_row * row_stride_b + dma_coff[j], dma_lds + stage_b + j * 1024u);
         }
     };
     // A whole tile inside segment A: constant per-lane offsets, only the base moves.
     auto dma_fast = [&](const char* base, uint32_t stage_b) {
 #pragma unroll
-        for (int j = 0; j < C::DMA_PER_WAVE; ++j) dma16(base, dma_off[j], dma_lds + stage_b + j * 1024u);
+        for (int j = 0; j < C::DMA_PER_WAVE; ++j) dma16<STREAM>(base, dma_off[j], dma_lds + stage_b + j * 1024u);
     };
     const int64_t tile_stride_b = BN * (int64_t)row_stride_b;
     const char* k_run = nullptr;                 // next K / V tile of the plain steps
@@ -272,7 +281,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
         for (int j = 0; j < C::DMA_PER_WAVE; ++j) {
             int r = dma_row + j * C::RPI;
             r = r < n_valid - 1 ? r : n_valid - 1;
-            dma16(base, (uint32_t)r * row_stride_b + dma_coff[j], dma_lds + stage_b + j * 1024u);
+            dma16<STREAM>(base, (uint32_t)r * row_stride_b + dma_coff[j], dma_lds + stage_b + j * 1024u);
         }
     };
     constexpr int DMA_PER_STEP = 2 * C::DMA_PER_WAVE;
@@ -590,11 +599,13 @@ hipError_t launch(const AttnProblem& p, const AttnPlan& plan, void* workspace, h
     }
     const int64_t nb = ik * plan.n_splits * plan.m_tiles;
     if (p.is_encode)
-        hipLaunchKernelGGL((attn_bf16_kernel<D, true, false>), dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
+        hipLaunchKernelGGL((attn_bf16_kernel<D, true, false, false>), dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
     else if (p.a_index)
-        hipLaunchKernelGGL((attn_bf16_kernel<D, false, true>), dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
+        hipLaunchKernelGGL((attn_bf16_kernel<D, false, true, false>), dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
+    else if (plan.m_tiles == 1)
+        hipLaunchKernelGGL((attn_bf16_kernel<D, false, false, true>), dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
     else
-        hipLaunchKernelGGL((attn_bf16_kernel<D, false, false>), dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
+        hipLaunchKernelGGL((attn_bf16_kernel<D, false, false, false>), dim3((unsigned)nb), dim3(THREADS), 0, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (plan.n_splits > 1) {
