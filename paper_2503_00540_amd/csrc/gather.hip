@@ -35,7 +35,7 @@ __global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(
 #pragma unroll
     for (int i = 0; i < UNROLL; ++i) {
         const size_t off = off0 + (size_t)i * GATHER_THREADS * 16;
-        if (off < frame_bytes) *reinterpret_cast<u32x4*>(dst + off) = v[i];
+        if (off < frame_bytes) __builtin_nontemporal_store(v[i], reinterpret_cast<u32x4*>(dst + off));
     }
 }
 
@@ -129,8 +129,8 @@ __global__ __launch_bounds__(GATHER_THREADS) void gather_rope_kernel(
                 }
             }
         }
-        *reinterpret_cast<u32x4*>(dst + off) = lo;
-        *reinterpret_cast<u32x4*>(dst + off + (size_t)half * (BF16 ? 2 : 4)) = hi;
+        __builtin_nontemporal_store(lo, reinterpret_cast<u32x4*>(dst + off));
+        __builtin_nontemporal_store(hi, reinterpret_cast<u32x4*>(dst + off + (size_t)half * (BF16 ? 2 : 4)));
     }
 }
 
