@@ -629,7 +629,10 @@ AttnPlan attn_bf16_plan(const AttnProblem& p) {
     int splits = 1;
     const int64_t target = 512;              // about two workgroups per CU
     if (base < target) {
-        splits = (int)((target + base - 1) / base);
+        // the largest split count that still fits one round of resident workgroups: one more
+        // workgroup than that costs a whole second round
+        splits = (int)(target / base);
+        if (splits < 1) splits = 1;
         // at least 8 tiles (256 keys) per split; 2 when only one wavefront per workgroup has rows
         // (a decode step), where latency rather than the pipeline's fill cost decides
         const int min_tiles = p.len_q * G <= WM ? 2 : 8;
