@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes of one encode launch from rocprofv3 --pmc FETCH_SIZE (x 2.0) and
 # WRITE_SIZE (x 1.0), KiB per dispatch; profiles/attn_bf16_encode_C1_hbm_traffic.txt
-MEASURED_TRAFFIC_BYTES = {"C1-7B-1layer": int((2.0 * 267461 + 351419) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"C1-7B-1layer": int((2.0 * 271777 + 351386) * 1024)}
 
 
 def encode_flops(w) -> float:
