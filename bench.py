@@ -27,8 +27,10 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_FP32_VALU_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes of one encode launch from rocprofv3 --pmc FETCH_SIZE (x 2.0) and
-# WRITE_SIZE (x 1.0), KiB per dispatch; profiles/attn_bf16_encode_C1_hbm_traffic.txt
+# HBM bytes of one encode launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (KiB per dispatch),
+# scaled by what the same counters read for the 1 GiB probe copy of the same run: reads x 2.0
+# (the counter prices this chip's 128-byte requests at 64 bytes), writes x 1.0.  The summary is
+# profiles/attn_bf16_encode_C1_hbm_traffic.txt
 MEASURED_TRAFFIC_BYTES = {"C1-7B-1layer": int((2.0 * 271777 + 351386) * 1024)}
 
 
