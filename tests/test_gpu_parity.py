@@ -268,6 +268,29 @@ def test_external_retrieval_matches_oracle(dim, n_frames, nq, tau, k):
         r.retrieve_external(torch.zeros((4, 6), device=DEV), torch.zeros((1, 6), device=DEV), 1)   # dim % 4
 
 
+@pytest.mark.parametrize("n_frames,k", [(4097, 64), (10000, 1), (10000, 4096), (70000, 333)],
+                         ids=["just-past-the-resident-limit", "k1", "largest-k", "70k-frames"])
+def test_topk_on_tables_longer_than_the_resident_limit(n_frames, k):
+    """More than 4,096 rows: the selection re-reads the scores from memory in every pass
+    instead of keeping keys in LDS.  Includes the largest k the call accepts."""
+    rng = np.random.default_rng(n_frames + k)
+    emb = rng.standard_normal((n_frames, 32)).astype(np.float32)
+    emb[::7] = emb[3]                                   # plenty of exact ties, also across the cut
+    qe = rng.standard_normal((2, 32)).astype(np.float32)
+    r = Rekv.for_workload(W.C1)
+    idx, n_sel, scores = r.retrieve_external(torch.from_numpy(emb).to(DEV), torch.from_numpy(qe).to(DEV), k,
+                                             want_scores=True)
+    for i in range(2):
+        ref_idx, ref_s = O.retrieve_external(emb, qe[i], k)
+        s_gpu = host(scores)[i]
+        assert np.abs(s_gpu - ref_s).max() < 1e-5
+        np.testing.assert_array_equal(idx[i].cpu().numpy(), O.topk_frames(s_gpu, k))   # exact on its own scores
+        check_topk(idx[i].cpu().numpy(), ref_s, k)
+        assert int(n_sel[i]) == k
+    with pytest.raises(RekvError):
+        r.retrieve_external(torch.from_numpy(emb).to(DEV), torch.from_numpy(qe).to(DEV), 4097)
+
+
 # ----------------------------------------------------------------------------------------
 # block-level retrieval
 # ----------------------------------------------------------------------------------------
