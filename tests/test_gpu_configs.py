@@ -216,3 +216,21 @@ def test_retrieval_and_qa_replay_from_a_hip_graph():
             assert torch.equal(out, ref) and torch.equal(idx, ref_idx)
             scratch = r.frame_keys(k, F)                 # eager library work between replays
             assert torch.equal(scratch, fk)
+
+
+def test_encode_with_the_papers_window_of_15k_tokens():
+    """The experiments' setting: local window of 15K tokens (neither a multiple of the 196-token
+    frame nor of the kernel's 32-key tile), one frame per chunk, 7B head layout.  Checked on
+    chunks before and after the window fills, one call for the stream and one call per chunk."""
+    w = W.C1.scaled(n_frames=100, name="C1-15k")
+    l_l = 15000
+    q, k, v = W.frames_q(w, 0, w.n_frames), W.frames_k(w, 0, w.n_frames), W.frames_v(w, 0, w.n_frames)
+    r = Rekv.for_workload(w)
+    dq, dk, dv = dev(q), dev(k), dev(v)
+    out = host(r.encode_chunk(dq, dk, dv, 0, w.l_x, w.n_frames, l_l))
+    for c in (76, 77, 99):                       # 76 * 196 = 14,896 < 15,000 <= 77 * 196
+        sl = slice(c * w.l_x, (c + 1) * w.l_x)
+        ref = O.encode_chunks(q[sl], k, v, c * w.l_x, w.l_x, 1, l_l)
+        assert np.abs(out[sl] - ref).max() < TOL, c
+        one = host(r.encode_chunk(dq[sl], dk, dv, c * w.l_x, w.l_x, 1, l_l))
+        assert np.abs(one - ref).max() < TOL, ("single", c)
