@@ -176,9 +176,10 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     const int row = m0 + wave * WM + col;        // this lane's query row
     const int tok = row / G;                      // its token inside the item
     const bool row_ok = row < m_rows;
-    // A wavefront whose 32 rows all lie past the last query row (a decode step has only G rows)
-    // keeps fetching tiles and joining the barriers but computes nothing.
-    const bool wave_active = ENCODE || m0 + wave * WM < m_rows;
+    // A wavefront whose 32 rows all lie past the last query row (the tail of the last row block;
+    // three of four in a decode step, which has only G rows) keeps fetching its share of the
+    // tiles and joining the barriers in a loop of its own, and computes nothing.
+    const bool wave_active = m0 + wave * WM < m_rows;
 
     // tile list: tiles_a tiles of segment A (the first a_full of them whole and unmasked), then
     // the causal tiles of segment B this row block can see
@@ -343,10 +344,6 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
             dma_any(ka, kb, t + 4, KL);
             dma_any(va, vb, t + 3, STAGES * TILE_B + VL);
         }
-        if (!wave_active) {
-            step_barrier<2 * DMA_PER_STEP>();
-            return;
-        }
         // All LDS operand reads of this step are issued first; the running-maximum work below
         // covers their latency, and the MFMAs then issue back to back.
         bf16x8 kf[D / 16];
@@ -454,6 +451,14 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
         // run the plain variant while all their tiles, and the tiles they fetch, are whole
         // unmasked tiles of segment A; the rest runs the general variant.
         int t = t_begin;
+        if (!wave_active) {
+            for (; t < t_end; ++t) {           // same loads into the same stages as the steps below
+                const uint32_t i4 = (uint32_t)(t - t_begin) & 3u;
+                dma_any(ka, kb, t + 4, i4 * TILE_B);
+                dma_any(va, vb, t + 3, VB + ((i4 + 3u) & 3u) * TILE_B);
+                step_barrier<2 * DMA_PER_STEP>();
+            }
+        }
         const int t_plain = (a_full < t_end ? a_full : t_end) - 8;   // t + 3 + 4 < a_full for the group
         const std::false_type general;
         const std::true_type plain;
