@@ -60,3 +60,32 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(rekv, "LIB_PATH", "/nonexistent/librekv.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         rekv.lib()
+
+
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """include/rekv.h compiles as C99 with every warning on, and a C program that names every
+    declared entry point links against librekv.so (nothing is called: no GPU here)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    names = _declared()
+    assert set(names) == set(rekv.SYMBOLS)
+    src = tmp_path / "use_abi.c"
+    body = "\n".join(f"    table[{i}] = (void (*)(void))&{n};" for i, n in enumerate(names))
+    src.write_text(f"""#include "rekv.h"
+#include <stdio.h>
+int main(void) {{
+    void (*table[{len(names)}])(void);
+{body}
+    rekv_shape shape = {{28, 4, 128, 196, REKV_BF16, 0.0f}};
+    printf("%d %d\\n", (int)sizeof(shape), table[0] != 0);
+    return 0;
+}}
+""")
+    lib_dir = os.path.dirname(rekv.LIB_PATH)
+    exe = tmp_path / "use_abi"
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src),
+           "-L", lib_dir, "-l:librekv.so", "-Wl,--unresolved-symbols=ignore-in-shared-libs", "-o", str(exe)]
+    p = subprocess.run(cmd, capture_output=True, text=True)
+    assert p.returncode == 0, p.stderr
