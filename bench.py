@@ -419,6 +419,11 @@ def main() -> None:
                             "what": "block vectors from the frame table + scores + top-k + frame list, one layer"},
         "box_peaks": dict(box_peaks(r, torch), encode_on_zero_inputs_TFLOPs=zero_tflops),
     }
+    bp = result["box_peaks"]
+    if w.dtype == "bf16" and bp.get("mfma_bf16_loop_TFLOPs"):
+        bp["encode_frac_of_mfma_loop"] = achieved / bp["mfma_bf16_loop_TFLOPs"]
+    bp["gather_frac_of_copy"] = (None if w.kv_on_host else
+                                 2 * gather_bytes / (ms["gather"] * 1e-3) / 1e9 / bp["copy_read_plus_write_GBs"])
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result))
