@@ -25,9 +25,14 @@
 // K(t+4) and V(t+3) are being fetched, so a load has three steps to land.  The four K and
 // four V stages sit in one LDS array and the loop is unrolled by four, so every stage is an
 // immediate offset of its ds_read.  Steps whose tiles are whole tiles of segment A run a
-// variant without masking and with constant load offsets.  Every step issues the same number of loads per wave (past the end of the tile
-// list the last tile is fetched again into a stage nobody reads), so "all but the newest
-// N loads have landed" is one s_waitcnt vmcnt(N).
+// variant without masking and with constant load offsets.  Every step issues the same number
+// of loads per wave (past the end of the tile list the last tile is fetched again into a stage
+// nobody reads), so "all but the newest N loads have landed" is one s_waitcnt vmcnt(N).
+//
+// Variants (template parameters): ENCODE - Eq. 1's window + chunk inside one cache, otherwise
+// Eq. 3's retrieved KV + text KV (question prefill and decode steps); INDEXED - segment A read
+// from the KV arena through a frame index list; STREAM - non-temporal tile loads when no
+// other workgroup reads the same keys.
 #include <type_traits>
 
 #include "common.h"
@@ -87,8 +92,6 @@ __device__ inline int xcd_remap(int bid, int nb) {
 
 __device__ inline void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
-// End of a pipeline step: this wave's loads except the newest N have landed, its LDS reads
-// have returned, then the workgroup barrier.  No fence: a fence would drain the newest loads.
 // One 16-byte-per-lane load from global memory straight into LDS: lane i's 16 bytes land at
 // lds_addr + 16 * i.  Written as asm so that the loads stay invisible to the compiler's
 // wait-count bookkeeping: with more than a handful of such loads in a loop it would drain
@@ -120,6 +123,8 @@ __device__ inline float pair_sum(float v) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// End of a pipeline step: this wave's loads except the newest N have landed, its LDS reads
+// have returned, then the workgroup barrier.  No fence: a fence would drain the newest loads.
 template <int N>
 __device__ inline void step_barrier() {
     static_assert(N >= 0 && N < 64, "vmcnt immediate");
