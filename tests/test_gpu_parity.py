@@ -622,6 +622,48 @@ def test_indexed_attention_matches_oracle_and_the_gathered_path(w, nq, n_ret_fra
         r.attention_indexed(dq, dk, dv, didx, n_ret_frames + 4, dkt, dvt, n_text)     # wider than the index rows
 
 
+def _random_qa_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        hkv = int(rng.choice([1, 2, 4, 8]))
+        g = int(rng.choice([1, 2, 4, 7, 8]))
+        n_text = int(rng.integers(1, 80))
+        cases.append(dict(dtype=str(rng.choice(["bf16", "bf16", "f32"])), hkv=hkv, hq=hkv * g,
+                          d=int(rng.choice([64, 128])), nf=int(rng.integers(1, 50)), nq=int(rng.integers(1, 4)),
+                          n_ret=int(rng.integers(1, 20)), n_text=n_text, n_new=int(rng.integers(1, n_text + 1)),
+                          slack=int(rng.integers(0, 5)), seed=i))
+    return cases
+
+
+@pytest.mark.parametrize("c", _random_qa_cases(24, 4242), ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
+def test_decode_and_indexed_attention_random_shapes(c):
+    """Seeded sweep of Eq. 3 shapes: the same random case through the gathered path and through the
+    in-place indexed path, both against the oracle, every output row."""
+    w = W.C1.scaled(dtype=c["dtype"], n_q_heads=c["hq"], n_kv_heads=c["hkv"], head_dim=c["d"],
+                    tokens_per_frame=c["nf"], n_frames=2 * c["n_ret"] + 3, name=f"rq{c['seed']}")
+    rng = np.random.default_rng(c["seed"])
+    k, v = W.frames_k(w, 0, w.n_frames), W.frames_v(w, 0, w.n_frames)
+    shape_q = (c["nq"], c["n_new"], w.n_q_heads, w.head_dim)
+    shape_t = (c["nq"], c["n_text"], w.n_kv_heads, w.head_dim)
+    rnd = lambda shape: (W.round_to_bf16(rng.standard_normal(shape)) if w.dtype == "bf16"
+                         else rng.standard_normal(shape).astype(np.float32).astype(np.float64))
+    q, kt, vt = rnd(shape_q), rnd(shape_t), rnd(shape_t)
+    idx = np.stack([rng.choice(w.n_frames, size=c["n_ret"], replace=False) for _ in range(c["nq"])]).astype(np.int32)
+    r = Rekv.for_workload(w)
+    pad = np.full((c["nq"], c["slack"], w.n_kv_heads, w.head_dim), np.nan)
+    dkt, dvt = dev(np.concatenate([kt, pad], axis=1), w), dev(np.concatenate([vt, pad], axis=1), w)
+    dk, dv, didx = dev(k, w), dev(v, w), torch.from_numpy(idx).to(DEV)
+    gk, gv = r.gather_kv(dk, dv, didx)
+    a = host(r.decode_attention(dev(q, w), gk, gv, dkt, dvt, c["n_text"]))
+    b = host(r.attention_indexed(dev(q, w), dk, dv, didx, c["n_ret"], dkt, dvt, c["n_text"]))
+    for i in range(c["nq"]):
+        rk, rv = O.gather_kv(k, v, idx[i], w.tokens_per_frame)
+        ref = O.decode_attention(q[i], rk, rv, kt[i], vt[i])
+        assert np.abs(a[i] - ref).max() < TOL[w.dtype]
+        assert np.abs(b[i] - ref).max() < TOL[w.dtype]
+
+
 def test_decode_attention_rejects_bad_arguments():
     w = W.C1
     r = Rekv.for_workload(w)
