@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0
 # scaled by what the same counters read for the 1 GiB probe copy of the same run: reads x 2.0
 # (the counter prices this chip's 128-byte requests at 64 bytes), writes x 1.0.  The summary is
 # profiles/attn_bf16_encode_C1_hbm_traffic.txt
-MEASURED_TRAFFIC_BYTES = {"C1-7B-1layer": int((2.0 * 271777 + 351386) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"C1-7B-1layer": int((2.0 * 267392 + 351251) * 1024)}
 
 
 def encode_flops(w) -> float:
