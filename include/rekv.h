@@ -22,9 +22,16 @@
  *     pointer after the call's work has completed on the stream.  The context owns
  *     a private workspace (split-KV partial results, pooled question vectors,
  *     scores), one side stream and two events.
+ *   - The workspace grows on demand: a call whose shapes need more than any call
+ *     before it on this context frees the old block and allocates a larger one
+ *     (hipFree + hipMalloc: the device is synchronised, and the call is not legal
+ *     under stream capture).  Run each shape once before capturing a graph or
+ *     entering a loop that must not allocate.  The workspace is shared by all calls on the context, so a context
+ *     serves one stream at a time.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     are asynchronous on it, except where a parameter says otherwise.
- *   - Every call returns a rekv_status; on error nothing has been launched and
+ *   - Every call returns a rekv_status.  Arguments are checked before anything is
+ *     launched (the one exception, host path 1 of rekv_gather_kv, says so there);
  *     rekv_last_error() describes the argument that was refused.  A context may be
  *     used by one host thread at a time.
  */
@@ -167,19 +174,23 @@ rekv_status rekv_expand_blocks(rekv_ctx* ctx, const int32_t* block_idx, int32_t 
                                int32_t* n_sel, void* stream);
 
 /*
- * Reload of the retrieved KV: copies the selected frames' key and value blocks into one
+ * Reload of the retrieved KV (overview figure, panel (c), and the text after Eq. 2: the
+ * key-value vectors of the r selected frames are brought back onto the GPU to serve as the
+ * context of question answering): copies the selected frames' key and value blocks into one
  * dense buffer per question, in the order idx gives them (ascending frame index).
  *
  *   src_k, src_v  [n_src_frames * N_f, Hkv, D] in HBM (src_on_host = 0) or in pinned host
  *                 memory (src_on_host = 1 or 2, host pointers; memory from hipHostMalloc)
- *   idx           [n_questions, k] int32 on the device; entries < 0 are skipped and their
- *                 destination block is zero-filled; entries >= n_src_frames are an error
- *                 only on the host path (the device path skips them likewise)
+ *   idx           [n_questions, k] int32 on the device; the destination block of an entry
+ *                 < 0 (the -1 padding of a short selection) is zero-filled; so is that of an
+ *                 entry >= n_src_frames on the device path and host path 2, while host
+ *                 path 1 reports such an entry as an error.  Pass the selection's n_sel to
+ *                 the attention call so that the zero-filled blocks are not attended to.
  *   dst_k, dst_v  [n_questions, k * N_f, Hkv, D] in HBM
  * Host path 1 (copy engine): idx is copied to the host (the call blocks until `stream`
- * reaches it), then one async copy per run of consecutive frames and tensor goes to the
- * context's side stream; `stream` waits on an event for their completion, so later work on
- * `stream` sees the data.
+ * reaches it, and that copy has run even if an entry is then refused), then one async copy
+ * per run of consecutive frames and tensor goes to the context's side stream; `stream` waits
+ * on an event for their completion, so later work on `stream` sees the data.
  * Host path 2 (zero-copy): the gather kernel itself reads the pinned arrays over the host
  * link, on the side stream, ordered after `stream` and joined back into it; the host does not
  * block and idx never leaves the device.  Out-of-range entries are skipped as on the device path.
@@ -189,10 +200,10 @@ rekv_status rekv_gather_kv(rekv_ctx* ctx, const void* src_k, const void* src_v,
                            int32_t n_questions, int32_t k, void* dst_k, void* dst_v, void* stream);
 
 /*
- * Reload of the retrieved KV with the position policy of the positional-encoding paragraph:
- * for question answering the original positions of the retrieved tokens are dropped and the
- * tokens count as regular consecutive tokens; the static variant gives all of them one
- * position.  Values are copied as by rekv_gather_kv; keys are rotated (rotary position
+ * Reload of the retrieved KV with the position policy of the "Positional Encoding" paragraph:
+ * for question answering the original stream positions of the retrieved tokens are dropped
+ * and the gathered tokens are numbered one after the other, like ordinary text; the static
+ * variant gives all of them one position.  Values are copied as by rekv_gather_kv; keys are rotated (rotary position
  * embedding: pair i of a head vector turns by position * base^(-2i/D)) to
  *   pos_mode 0 (consecutive): position pos_offset + j for gathered token j of the question,
  *   pos_mode 1 (static):      position pos_offset for every token.
@@ -218,11 +229,17 @@ rekv_status rekv_gather_kv_rope(rekv_ctx* ctx, const void* src_k, const void* sr
  *
  *   q, out          [n_questions, N_q, Hq, D]
  *   k_ret, v_ret    [n_questions, n_ret_tokens, Hkv, D]   (n_ret_tokens may be 0)
+ *   n_sel           device int32 [n_questions] or NULL: frames actually retrieved for each
+ *                   question (the n_sel of rekv_retrieve_topk / rekv_expand_blocks).  Question
+ *                   i attends to its first min(n_sel[i] * N_f, n_ret_tokens) retrieved tokens
+ *                   only, so the padding of a selection shorter than k (young stream, ragged
+ *                   last block) stays out of the softmax.  NULL: all n_ret_tokens are valid.
  *   k_self, v_self  [n_questions, N_q, Hkv, D]
  */
 rekv_status rekv_qa_attention(rekv_ctx* ctx, const void* q, const void* k_ret, const void* v_ret,
-                              int32_t n_ret_tokens, const void* k_self, const void* v_self,
-                              int32_t n_questions, int32_t n_q_tokens, void* out, void* stream);
+                              int32_t n_ret_tokens, const int32_t* n_sel, const void* k_self,
+                              const void* v_self, int32_t n_questions, int32_t n_q_tokens, void* out,
+                              void* stream);
 
 /*
  * Answer decoding over the retrieved KV, Eq. 3 with X = the token(s) being decoded: the
@@ -234,13 +251,14 @@ rekv_status rekv_qa_attention(rekv_ctx* ctx, const void* q, const void* k_ret, c
  *
  *   q, out          [n_questions, n_new_tokens, Hq, D]
  *   k_ret, v_ret    [n_questions, n_ret_tokens, Hkv, D]   (n_ret_tokens may be 0)
+ *   n_sel           as in rekv_qa_attention (device int32 [n_questions] or NULL)
  *   k_text, v_text  [n_questions, text_stride, Hkv, D], the first n_text_tokens rows of each
  *                   question valid (text_stride >= n_text_tokens >= n_new_tokens >= 1)
  */
 rekv_status rekv_decode_attention(rekv_ctx* ctx, const void* q, const void* k_ret, const void* v_ret,
-                                  int32_t n_ret_tokens, const void* k_text, const void* v_text,
-                                  int64_t text_stride, int32_t n_text_tokens, int32_t n_questions,
-                                  int32_t n_new_tokens, void* out, void* stream);
+                                  int32_t n_ret_tokens, const int32_t* n_sel, const void* k_text,
+                                  const void* v_text, int64_t text_stride, int32_t n_text_tokens,
+                                  int32_t n_questions, int32_t n_new_tokens, void* out, void* stream);
 
 /*
  * Eq. 3 straight from the KV arena: the same attention as rekv_decode_attention (hence as
@@ -252,20 +270,24 @@ rekv_status rekv_decode_attention(rekv_ctx* ctx, const void* q, const void* k_re
  *   q, out          [n_questions, n_new_tokens, Hq, D]
  *   k_src, v_src    [n_src_frames * N_f, Hkv, D] in HBM, each below 4 GiB
  *   idx             [n_questions, idx_stride] int32 on the device, idx_stride >= n_ret_frames;
- *                   the first n_ret_frames entries of every row must be frames of the arena
- *                   (entries outside [0, n_src_frames) are clamped into it, never followed out
- *                   of bounds); 1 <= n_ret_frames <= 1024
+ *                   the first min(n_ret_frames, n_sel[i]) entries of row i must be frames of
+ *                   the arena (entries outside [0, n_src_frames) are clamped into it, never
+ *                   followed out of bounds); 1 <= n_ret_frames <= 1024
+ *   n_sel           device int32 [n_questions] or NULL: entries of each row that are real
+ *                   selections (rekv_retrieve_topk's n_sel); the -1 padding after them is
+ *                   neither read nor attended to.  NULL: all n_ret_frames entries are used.
  *   k_text, v_text, text_stride, n_text_tokens, n_new_tokens   as in rekv_decode_attention
  */
 rekv_status rekv_attention_indexed(rekv_ctx* ctx, const void* q, const void* k_src, const void* v_src,
                                    int32_t n_src_frames, const int32_t* idx, int64_t idx_stride,
-                                   int32_t n_ret_frames, const void* k_text, const void* v_text,
+                                   int32_t n_ret_frames, const int32_t* n_sel, const void* k_text, const void* v_text,
                                    int64_t text_stride, int32_t n_text_tokens, int32_t n_questions,
                                    int32_t n_new_tokens, void* out, void* stream);
 
 /*
- * Offload of encoded KV to RAM (the paper stores all video KV and moves what leaves the
- * local window off the GPU).  Copies n_frames whole frames of K and V, starting at frame
+ * Offload of encoded KV to RAM (the paragraph after Eq. 1: every frame's KV is kept, and what
+ * leaves the local window moves off the GPU; appendix "Multi-processing Serving": the encoder
+ * process hands the stream's KV to the answering processes through host memory).  Copies n_frames whole frames of K and V, starting at frame
  * first_frame of the device arrays, to the same frame positions of the pinned host arrays.
  * The copies run on the context's side stream after everything queued on `stream` so far;
  * `stream` does not wait for them.  rekv_offload_wait() blocks the host until all offloads

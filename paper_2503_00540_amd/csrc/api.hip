@@ -160,7 +160,7 @@ rekv_status rekv_encode_chunk(rekv_ctx* c, const void* q, const void* k_cache, c
 }
 
 rekv_status rekv_qa_attention(rekv_ctx* c, const void* q, const void* k_ret, const void* v_ret,
-                              int32_t n_ret_tokens, const void* k_self, const void* v_self,
+                              int32_t n_ret_tokens, const int32_t* n_sel, const void* k_self, const void* v_self,
                               int32_t n_questions, int32_t n_q_tokens, void* out, void* stream) {
     if (!c) return REKV_ERR_INVALID_ARG;
     if (!q || !k_self || !v_self || !out || (n_ret_tokens > 0 && (!k_ret || !v_ret)))
@@ -178,6 +178,7 @@ rekv_status rekv_qa_attention(rekv_ctx* c, const void* q, const void* k_ret, con
     p.k_a = k_ret ? k_ret : k_self; p.v_a = v_ret ? v_ret : v_self; p.k_b = k_self; p.v_b = v_self;
     p.first_token = 0; p.l_l = 0; p.len_a = n_ret_tokens; p.len_b = n_q_tokens; p.len_q = n_q_tokens;
     p.b_stride = n_q_tokens;
+    p.a_valid_frames = n_sel; p.n_f = c->shape.tokens_per_frame;
     p.n_items = n_questions; p.is_encode = 0;
     p.n_q_heads = c->shape.n_q_heads; p.n_kv_heads = c->shape.n_kv_heads; p.head_dim = c->shape.head_dim;
     p.scale = c->scale;
@@ -185,27 +186,29 @@ rekv_status rekv_qa_attention(rekv_ctx* c, const void* q, const void* k_ret, con
 }
 
 rekv_status rekv_decode_attention(rekv_ctx* c, const void* q, const void* k_ret, const void* v_ret,
-                                  int32_t n_ret_tokens, const void* k_text, const void* v_text,
-                                  int64_t text_stride, int32_t n_text_tokens, int32_t n_questions,
-                                  int32_t n_new_tokens, void* out, void* stream) {
+                                  int32_t n_ret_tokens, const int32_t* n_sel, const void* k_text,
+                                  const void* v_text, int64_t text_stride, int32_t n_text_tokens,
+                                  int32_t n_questions, int32_t n_new_tokens, void* out, void* stream) {
+    const char* fn = "rekv_decode_attention";
     if (!c) return REKV_ERR_INVALID_ARG;
     if (!q || !k_text || !v_text || !out || (n_ret_tokens > 0 && (!k_ret || !v_ret)))
-        return fail(c, REKV_ERR_INVALID_ARG, "rekv_decode_attention: null pointer");
+        return fail(c, REKV_ERR_INVALID_ARG, "%s: null pointer", fn);
     if (!aligned16(q) || !aligned16(k_ret) || !aligned16(v_ret) || !aligned16(k_text) || !aligned16(v_text) || !aligned16(out))
-        return fail(c, REKV_ERR_INVALID_ARG, "rekv_decode_attention: pointers must be 16-byte aligned");
+        return fail(c, REKV_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", fn);
     if (n_ret_tokens < 0 || n_questions <= 0 || n_new_tokens <= 0 || n_text_tokens < n_new_tokens ||
         text_stride < n_text_tokens)
         return fail(c, REKV_ERR_INVALID_ARG,
-                    "rekv_decode_attention: n_ret_tokens=%d n_questions=%d n_new_tokens=%d n_text_tokens=%d text_stride=%lld",
+                    "%s: n_ret_tokens=%d n_questions=%d n_new_tokens=%d n_text_tokens=%d text_stride=%lld", fn,
                     n_ret_tokens, n_questions, n_new_tokens, n_text_tokens, (long long)text_stride);
     if ((int64_t)n_new_tokens * (c->shape.n_q_heads / c->shape.n_kv_heads) > 0x3FFFFFFF)
-        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_decode_attention: %d new tokens are too many", n_new_tokens);
+        return fail(c, REKV_ERR_UNSUPPORTED, "%s: %d new tokens are too many", fn, n_new_tokens);
     rekv::AttnProblem p;
     memset(&p, 0, sizeof(p));
     p.q = q; p.out = out;
     p.k_a = k_ret ? k_ret : k_text; p.v_a = v_ret ? v_ret : v_text; p.k_b = k_text; p.v_b = v_text;
     p.first_token = 0; p.l_l = 0; p.len_a = n_ret_tokens; p.len_b = n_text_tokens; p.len_q = n_new_tokens;
     p.b_stride = text_stride;
+    p.a_valid_frames = n_sel; p.n_f = c->shape.tokens_per_frame;
     p.n_items = n_questions; p.is_encode = 0;
     p.n_q_heads = c->shape.n_q_heads; p.n_kv_heads = c->shape.n_kv_heads; p.head_dim = c->shape.head_dim;
     p.scale = c->scale;
@@ -214,7 +217,7 @@ rekv_status rekv_decode_attention(rekv_ctx* c, const void* q, const void* k_ret,
 
 rekv_status rekv_attention_indexed(rekv_ctx* c, const void* q, const void* k_src, const void* v_src,
                                    int32_t n_src_frames, const int32_t* idx, int64_t idx_stride,
-                                   int32_t n_ret_frames, const void* k_text, const void* v_text,
+                                   int32_t n_ret_frames, const int32_t* n_sel, const void* k_text, const void* v_text,
                                    int64_t text_stride, int32_t n_text_tokens, int32_t n_questions,
                                    int32_t n_new_tokens, void* out, void* stream) {
     if (!c) return REKV_ERR_INVALID_ARG;
@@ -248,6 +251,7 @@ rekv_status rekv_attention_indexed(rekv_ctx* c, const void* q, const void* k_src
     p.n_q_heads = c->shape.n_q_heads; p.n_kv_heads = c->shape.n_kv_heads; p.head_dim = c->shape.head_dim;
     p.scale = c->scale;
     p.a_index = idx; p.a_index_stride = idx_stride; p.n_f = (int32_t)n_f; p.n_src_frames = n_src_frames;
+    p.a_valid_frames = n_sel;
     return run_attention(c, p, static_cast<hipStream_t>(stream));
 }
 
@@ -268,8 +272,8 @@ rekv_status rekv_retrieve_topk(rekv_ctx* c, const float* frame_keys, int64_t fra
                                float* scores, void* stream) {
     if (!c) return REKV_ERR_INVALID_ARG;
     if (!frame_keys || !q_question || !idx) return fail(c, REKV_ERR_INVALID_ARG, "rekv_retrieve_topk: null pointer");
-    if (!aligned16(frame_keys) || frame_keys_stride < 0 || frame_keys_stride % 4 != 0)
-        return fail(c, REKV_ERR_INVALID_ARG, "rekv_retrieve_topk: frame_keys must be 16-byte aligned and its stride a non-negative multiple of 4");
+    if (!aligned16(frame_keys) || !aligned16(q_question) || frame_keys_stride < 0 || frame_keys_stride % 4 != 0)
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_retrieve_topk: frame_keys and q_question must be 16-byte aligned, the stride a non-negative multiple of 4");
     if (n_frames <= 0 || n_questions <= 0 || n_q_tokens <= 0 || k <= 0 || k > 4096)
         return fail(c, REKV_ERR_INVALID_ARG, "rekv_retrieve_topk: n_frames=%d n_questions=%d n_q_tokens=%d k=%d (1..4096)",
                     n_frames, n_questions, n_q_tokens, k);

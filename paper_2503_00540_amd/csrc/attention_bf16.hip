@@ -451,6 +451,11 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
             qk(kf0, s_a);
         }
         step_barrier<0>();         // K(t_begin) is consumed: its stage is refilled in the first step
+        // Everything this wave has loaded so far (the Q fragments among it) has landed.  Saying so in
+        // a form the compiler's wait-count bookkeeping sees keeps it from putting a vmcnt(0) in front
+        // of the loop's first MFMA, where it would also wait for the tile loads the loop has just
+        // issued (those are asm and invisible to it).
+        wait_vmem();
         // Step i (mod 4) of this workgroup: S(t) in s_a / s_b alternately, K(t+1) in stage i+1,
         // V(t) in stage i; K(t+4) goes to stage i, V(t+3) to stage i+3.  Groups of four steps
         // run the plain variant while all their tiles, and the tiles they fetch, are whole

@@ -40,14 +40,18 @@ struct AttnProblem {
     int64_t a_index_stride;
     int32_t n_f;              // tokens per frame
     int32_t n_src_frames;     // frames in the arena; index entries are clamped into [0, n_src_frames)
+    // QA / decode: frames actually retrieved per item (device int32 [n_items], NULL = all): item i
+    // attends to the first min(a_valid_frames[i] * n_f, len_a) tokens of its segment A only.
+    const int32_t* a_valid_frames;
 };
 
-// Resolves one item's segment bases (in elements) and lengths.  Host and device.
+// Resolves one item's segment bases (in elements) and lengths.  Device only: it reads the
+// per-item count of retrieved frames.
 struct ItemSegs {
     int64_t a_off, b_off;  // token offsets into k_a/v_a and k_b/v_b
     int32_t len_a;
 };
-__host__ __device__ inline ItemSegs item_segments(const AttnProblem& p, int item) {
+__device__ inline ItemSegs item_segments(const AttnProblem& p, int item) {
     ItemSegs s;
     if (p.is_encode) {
         const int64_t t0 = p.first_token + (int64_t)item * p.len_b;
@@ -59,6 +63,11 @@ __host__ __device__ inline ItemSegs item_segments(const AttnProblem& p, int item
         s.a_off = p.a_index ? 0 : (int64_t)item * p.len_a;
         s.b_off = (int64_t)item * p.b_stride;
         s.len_a = p.len_a;
+        if (p.a_valid_frames) {
+            const int32_t nv = p.a_valid_frames[item];
+            const int64_t lim = (int64_t)(nv > 0 ? nv : 0) * p.n_f;
+            if (lim < s.len_a) s.len_a = (int32_t)lim;
+        }
     }
     return s;
 }

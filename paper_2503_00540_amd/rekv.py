@@ -63,17 +63,17 @@ def lib() -> ctypes.CDLL:
                                      c_int32, c_void_p, c_void_p, c_void_p, c_void_p]
     L.rekv_gather_kv.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_int32,
                                  c_int32, c_void_p, c_void_p, c_void_p]
-    L.rekv_qa_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p,
+    L.rekv_qa_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p,
                                     c_int32, c_int32, c_void_p, c_void_p]
     L.rekv_retrieve_external.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_int32, c_float,
                                          c_int32, c_void_p, c_void_p, c_void_p, c_void_p]
     L.rekv_block_keys.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p]
     L.rekv_expand_blocks.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_void_p,
                                      c_void_p, c_void_p]
-    L.rekv_decode_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p,
+    L.rekv_decode_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p,
                                         c_int64, c_int32, c_int32, c_int32, c_void_p, c_void_p]
     L.rekv_attention_indexed.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_int64,
-                                         c_int32, c_void_p, c_void_p, c_int64, c_int32, c_int32, c_int32,
+                                         c_int32, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32, c_int32,
                                          c_void_p, c_void_p]
     L.rekv_gather_kv_rope.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_int32, c_int32, c_void_p,
                                       c_void_p, ctypes.c_double, c_int32, c_int32, c_int64, c_int32, c_int64, c_void_p]
@@ -144,6 +144,13 @@ class Rekv:
         if tuple(t.shape[-len(last):]) != tuple(last):
             raise ValueError(f"{name} has shape {tuple(t.shape)}, expected trailing {tuple(last)}")
         return t.data_ptr()
+
+    def _n_sel(self, n_sel, nq: int):
+        if n_sel is None:
+            return None
+        if not n_sel.is_cuda or n_sel.dtype != torch.int32 or not n_sel.is_contiguous() or n_sel.numel() != nq:
+            raise ValueError("n_sel must be a contiguous device int32 tensor with one entry per question")
+        return n_sel.data_ptr()
 
     # -- the entry points -----------------------------------------------------------------
     def encode_chunk(self, q, k_cache, v_cache, first_token: int, l_x: int, n_chunks: int, l_l: int,
@@ -283,7 +290,7 @@ class Rekv:
             int(src_rotated), src_pos_offset, _stream()))
         return dst_k, dst_v
 
-    def qa_attention(self, q, k_ret, v_ret, k_self, v_self, out=None):
+    def qa_attention(self, q, k_ret, v_ret, k_self, v_self, out=None, n_sel=None):
         """q [n_questions, N_q, Hq, D]; k_ret/v_ret [n_questions, n_ret, Hkv, D]; k_self/v_self
         [n_questions, N_q, Hkv, D]."""
         qh, kh = (self.n_q_heads, self.head_dim), (self.n_kv_heads, self.head_dim)
@@ -301,12 +308,12 @@ class Rekv:
         self._check(self._lib.rekv_qa_attention(
             self._h, self._dev(q, last=qh, name="q"),
             self._dev(k_ret, last=kh, name="k_ret") if n_ret else None,
-            self._dev(v_ret, last=kh, name="v_ret") if n_ret else None, n_ret,
+            self._dev(v_ret, last=kh, name="v_ret") if n_ret else None, n_ret, self._n_sel(n_sel, nq),
             self._dev(k_self, last=kh, name="k_self"), self._dev(v_self, last=kh, name="v_self"),
             nq, n_q_tokens, self._dev(out, last=qh, name="out"), _stream()))
         return out
 
-    def decode_attention(self, q, k_ret, v_ret, k_text, v_text, n_text_tokens: int, out=None):
+    def decode_attention(self, q, k_ret, v_ret, k_text, v_text, n_text_tokens: int, out=None, n_sel=None):
         """q [n_questions, n_new, Hq, D]; k_ret/v_ret [n_questions, n_ret, Hkv, D]; k_text/v_text
         [n_questions, text_stride, Hkv, D] whose first n_text_tokens rows are valid and end with
         the new tokens' own K/V."""
@@ -325,13 +332,13 @@ class Rekv:
         self._check(self._lib.rekv_decode_attention(
             self._h, self._dev(q, last=qh, name="q"),
             self._dev(k_ret, last=kh, name="k_ret") if n_ret else None,
-            self._dev(v_ret, last=kh, name="v_ret") if n_ret else None, n_ret,
+            self._dev(v_ret, last=kh, name="v_ret") if n_ret else None, n_ret, self._n_sel(n_sel, nq),
             self._dev(k_text, last=kh, name="k_text"), self._dev(v_text, last=kh, name="v_text"),
             stride, n_text_tokens, nq, n_new, self._dev(out, last=qh, name="out"), _stream()))
         return out
 
     def attention_indexed(self, q, k_src, v_src, idx, n_ret_frames: int, k_text, v_text, n_text_tokens: int,
-                          n_src_frames: int | None = None, out=None):
+                          n_src_frames: int | None = None, out=None, n_sel=None):
         """Eq. 3 with the retrieved KV read in place: q [n_questions, n_new, Hq, D]; k_src/v_src the
         arena [tokens, Hkv, D]; idx [n_questions, >= n_ret_frames] int32; k_text/v_text
         [n_questions, text_stride, Hkv, D]."""
@@ -352,7 +359,7 @@ class Rekv:
         self._check(self._lib.rekv_attention_indexed(
             self._h, self._dev(q, last=qh, name="q"), self._dev(k_src, last=kh, name="k_src"),
             self._dev(v_src, last=kh, name="v_src"), nf, idx.data_ptr(), idx.shape[1], n_ret_frames,
-            self._dev(k_text, last=kh, name="k_text"), self._dev(v_text, last=kh, name="v_text"),
+            self._n_sel(n_sel, nq), self._dev(k_text, last=kh, name="k_text"), self._dev(v_text, last=kh, name="v_text"),
             k_text.shape[1], n_text_tokens, nq, n_new, self._dev(out, last=qh, name="out"), _stream()))
         return out
 
