@@ -26,7 +26,8 @@
  *     before it on this context frees the old block and allocates a larger one
  *     (hipFree + hipMalloc: the device is synchronised, and the call is not legal
  *     under stream capture).  Run each shape once before capturing a graph or
- *     entering a loop that must not allocate.  The workspace is shared by all calls on the context, so a context
+ *     entering a loop that must not allocate; rekv_decode_attention_noalloc never
+ *     allocates.  The workspace is shared by all calls on the context, so a context
  *     serves one stream at a time.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     are asynchronous on it, except where a parameter says otherwise.
@@ -259,6 +260,24 @@ rekv_status rekv_decode_attention(rekv_ctx* ctx, const void* q, const void* k_re
                                   int32_t n_ret_tokens, const int32_t* n_sel, const void* k_text,
                                   const void* v_text, int64_t text_stride, int32_t n_text_tokens,
                                   int32_t n_questions, int32_t n_new_tokens, void* out, void* stream);
+
+/*
+ * rekv_decode_attention for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops that decode token after token, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels, same result.  The split-KV partial results go to a static
+ * device array of 33 MiB inside the library (one copy per GPU, held until the process ends)
+ * instead of the context's growable workspace, so the call never allocates, frees or
+ * synchronises.  A launch that would need more scratch than that is refused with
+ * REKV_ERR_UNSUPPORTED (fp32 contexts use no scratch at all).  Every call on a GPU shares that
+ * GPU's array: calls that overlap in time on one GPU - other streams, other contexts - race;
+ * calls ordered on one stream are safe.  Nothing in the array needs to start at zero: a launch
+ * writes every partial result it later reads.
+ */
+rekv_status rekv_decode_attention_noalloc(rekv_ctx* ctx, const void* q, const void* k_ret,
+                                          const void* v_ret, int32_t n_ret_tokens, const int32_t* n_sel,
+                                          const void* k_text, const void* v_text, int64_t text_stride,
+                                          int32_t n_text_tokens, int32_t n_questions,
+                                          int32_t n_new_tokens, void* out, void* stream);
 
 /*
  * Eq. 3 straight from the KV arena: the same attention as rekv_decode_attention (hence as

@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "common.h"
@@ -14,6 +15,7 @@ struct rekv_ctx {
     int device;
     void* ws;             // workspace: split-KV partials, or pooled questions + scores
     size_t ws_bytes;
+    void* scratch;        // this device's copy of the static scratch array
     hipStream_t side;     // host<->device copies of offloaded KV
     hipEvent_t ev_main;   // recorded on the caller's stream, waited on by the side stream
     hipEvent_t ev_side;   // recorded on the side stream, waited on by the caller's stream
@@ -22,9 +24,36 @@ struct rekv_ctx {
     char err[512];
 };
 
+// Scratch of the allocation-free entry point (rekv_decode_attention_noalloc): the split-KV
+// partial results of one launch.  One copy per GPU, held until the process ends; every call on a
+// GPU shares it.  The bf16 plan never asks for more: at most 512 workgroups x 128 rows x
+// (D + 2) floats when the key range is split.
+constexpr size_t NOALLOC_SCRATCH_BYTES = (size_t)33 << 20;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local char g_create_err[512] = "";
+
+// Device address of `scratch` on each GPU (the array's name is only a host-side handle).
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// Looks the address up once per device; that device must be current.
+hipError_t scratch_address(int device, void** out) {
+    *out = nullptr;
+    if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 rekv_status fail(rekv_ctx* ctx, rekv_status code, const char* fmt, ...) {
     char* dst = ctx ? ctx->err : g_create_err;
@@ -64,7 +93,10 @@ rekv_status reserve(rekv_ctx* c, size_t bytes) {
     return REKV_OK;
 }
 
-rekv_status run_attention(rekv_ctx* c, const rekv::AttnProblem& p, hipStream_t stream) {
+// fixed_ws != NULL: the launch may use only that buffer of fixed_ws_bytes (no allocation);
+// otherwise the context's workspace grows as needed.
+rekv_status run_attention(rekv_ctx* c, const rekv::AttnProblem& p, hipStream_t stream, void* fixed_ws = nullptr,
+                          size_t fixed_ws_bytes = 0) {
     if (c->shape.dtype == REKV_F32) {
         if (p.n_items > 65535)
             return fail(c, REKV_ERR_UNSUPPORTED, "fp32 attention takes at most 65535 chunks/questions per call");
@@ -74,9 +106,17 @@ rekv_status run_attention(rekv_ctx* c, const rekv::AttnProblem& p, hipStream_t s
     const rekv::AttnPlan plan = rekv::attn_bf16_plan(p);
     const int64_t blocks = (int64_t)p.n_items * p.n_kv_heads * plan.m_tiles * plan.n_splits;
     if (blocks > 0x7FFFFFFF) return fail(c, REKV_ERR_UNSUPPORTED, "attention grid of %lld workgroups", (long long)blocks);
-    rekv_status s = reserve(c, plan.workspace_bytes);
-    if (s != REKV_OK) return s;
-    hipError_t e = rekv::attn_bf16_launch(p, plan, c->ws, stream);
+    void* ws = fixed_ws;
+    if (fixed_ws) {
+        if (plan.workspace_bytes > fixed_ws_bytes)
+            return fail(c, REKV_ERR_UNSUPPORTED, "this launch needs %zu bytes of scratch, the static buffer holds %zu",
+                        plan.workspace_bytes, fixed_ws_bytes);
+    } else {
+        rekv_status s = reserve(c, plan.workspace_bytes);
+        if (s != REKV_OK) return s;
+        ws = c->ws;
+    }
+    hipError_t e = rekv::attn_bf16_launch(p, plan, ws, stream);
     return e == hipSuccess ? REKV_OK : fail_hip(c, "bf16 attention launch", e);
 }
 
@@ -109,6 +149,7 @@ rekv_status rekv_create(const rekv_shape* shape, rekv_ctx** out) {
     c->shape = *shape;
     c->scale = shape->softmax_scale > 0.f ? shape->softmax_scale : 1.0f / sqrtf((float)shape->head_dim);
     hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess) e = scratch_address(c->device, &c->scratch);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_main, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_side, hipEventDisableTiming);
@@ -185,11 +226,12 @@ rekv_status rekv_qa_attention(rekv_ctx* c, const void* q, const void* k_ret, con
     return run_attention(c, p, static_cast<hipStream_t>(stream));
 }
 
-rekv_status rekv_decode_attention(rekv_ctx* c, const void* q, const void* k_ret, const void* v_ret,
-                                  int32_t n_ret_tokens, const int32_t* n_sel, const void* k_text,
-                                  const void* v_text, int64_t text_stride, int32_t n_text_tokens,
-                                  int32_t n_questions, int32_t n_new_tokens, void* out, void* stream) {
-    const char* fn = "rekv_decode_attention";
+// Shared body of rekv_decode_attention and its allocation-free variant.
+static rekv_status decode_attention(rekv_ctx* c, const char* fn, bool no_alloc, const void* q, const void* k_ret,
+                                    const void* v_ret, int32_t n_ret_tokens, const int32_t* n_sel,
+                                    const void* k_text, const void* v_text, int64_t text_stride,
+                                    int32_t n_text_tokens, int32_t n_questions, int32_t n_new_tokens, void* out,
+                                    void* stream) {
     if (!c) return REKV_ERR_INVALID_ARG;
     if (!q || !k_text || !v_text || !out || (n_ret_tokens > 0 && (!k_ret || !v_ret)))
         return fail(c, REKV_ERR_INVALID_ARG, "%s: null pointer", fn);
@@ -212,7 +254,24 @@ rekv_status rekv_decode_attention(rekv_ctx* c, const void* q, const void* k_ret,
     p.n_items = n_questions; p.is_encode = 0;
     p.n_q_heads = c->shape.n_q_heads; p.n_kv_heads = c->shape.n_kv_heads; p.head_dim = c->shape.head_dim;
     p.scale = c->scale;
+    if (no_alloc) return run_attention(c, p, static_cast<hipStream_t>(stream), c->scratch, NOALLOC_SCRATCH_BYTES);
     return run_attention(c, p, static_cast<hipStream_t>(stream));
+}
+
+rekv_status rekv_decode_attention(rekv_ctx* c, const void* q, const void* k_ret, const void* v_ret,
+                                  int32_t n_ret_tokens, const int32_t* n_sel, const void* k_text,
+                                  const void* v_text, int64_t text_stride, int32_t n_text_tokens,
+                                  int32_t n_questions, int32_t n_new_tokens, void* out, void* stream) {
+    return decode_attention(c, "rekv_decode_attention", false, q, k_ret, v_ret, n_ret_tokens, n_sel, k_text, v_text,
+                            text_stride, n_text_tokens, n_questions, n_new_tokens, out, stream);
+}
+
+rekv_status rekv_decode_attention_noalloc(rekv_ctx* c, const void* q, const void* k_ret, const void* v_ret,
+                                          int32_t n_ret_tokens, const int32_t* n_sel, const void* k_text,
+                                          const void* v_text, int64_t text_stride, int32_t n_text_tokens,
+                                          int32_t n_questions, int32_t n_new_tokens, void* out, void* stream) {
+    return decode_attention(c, "rekv_decode_attention_noalloc", true, q, k_ret, v_ret, n_ret_tokens, n_sel, k_text,
+                            v_text, text_stride, n_text_tokens, n_questions, n_new_tokens, out, stream);
 }
 
 rekv_status rekv_attention_indexed(rekv_ctx* c, const void* q, const void* k_src, const void* v_src,

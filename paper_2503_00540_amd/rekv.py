@@ -23,7 +23,7 @@ _DTYPES = {"f32": (REKV_F32, torch.float32), "bf16": (REKV_BF16, torch.bfloat16)
 # Every entry point include/rekv.h declares.
 SYMBOLS = ("rekv_create", "rekv_destroy", "rekv_last_error", "rekv_encode_chunk",
            "rekv_frame_keys", "rekv_retrieve_topk", "rekv_gather_kv", "rekv_qa_attention",
-           "rekv_decode_attention", "rekv_block_keys", "rekv_expand_blocks", "rekv_retrieve_external", "rekv_attention_indexed", "rekv_gather_kv_rope",
+           "rekv_decode_attention", "rekv_decode_attention_noalloc", "rekv_block_keys", "rekv_expand_blocks", "rekv_retrieve_external", "rekv_attention_indexed", "rekv_gather_kv_rope",
            "rekv_offload_kv", "rekv_offload_wait", "rekv_probe_copy", "rekv_probe_mfma")
 
 
@@ -72,6 +72,7 @@ def lib() -> ctypes.CDLL:
                                      c_void_p, c_void_p]
     L.rekv_decode_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p,
                                         c_int64, c_int32, c_int32, c_int32, c_void_p, c_void_p]
+    L.rekv_decode_attention_noalloc.argtypes = L.rekv_decode_attention.argtypes
     L.rekv_attention_indexed.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_int64,
                                          c_int32, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32, c_int32,
                                          c_void_p, c_void_p]
@@ -313,7 +314,8 @@ class Rekv:
             nq, n_q_tokens, self._dev(out, last=qh, name="out"), _stream()))
         return out
 
-    def decode_attention(self, q, k_ret, v_ret, k_text, v_text, n_text_tokens: int, out=None, n_sel=None):
+    def decode_attention(self, q, k_ret, v_ret, k_text, v_text, n_text_tokens: int, out=None, n_sel=None,
+                         no_alloc: bool = False):
         """q [n_questions, n_new, Hq, D]; k_ret/v_ret [n_questions, n_ret, Hkv, D]; k_text/v_text
         [n_questions, text_stride, Hkv, D] whose first n_text_tokens rows are valid and end with
         the new tokens' own K/V."""
@@ -329,7 +331,8 @@ class Rekv:
         out = torch.empty_like(q) if out is None else out
         if out.shape != q.shape:
             raise ValueError("out must have the shape of q")
-        self._check(self._lib.rekv_decode_attention(
+        fn = self._lib.rekv_decode_attention_noalloc if no_alloc else self._lib.rekv_decode_attention
+        self._check(fn(
             self._h, self._dev(q, last=qh, name="q"),
             self._dev(k_ret, last=kh, name="k_ret") if n_ret else None,
             self._dev(v_ret, last=kh, name="v_ret") if n_ret else None, n_ret, self._n_sel(n_sel, nq),

@@ -52,6 +52,7 @@ def test_entry_points_refuse_a_null_context():
     assert L.rekv_gather_kv(None, None, None, 0, 1, None, 1, 1, None, None, None) == 1
     assert L.rekv_qa_attention(None, None, None, None, 0, None, None, None, 1, 1, None, None) == 1
     assert L.rekv_decode_attention(None, None, None, None, 0, None, None, None, 1, 1, 1, 1, None, None) == 1
+    assert L.rekv_decode_attention_noalloc(None, None, None, None, 0, None, None, None, 1, 1, 1, 1, None, None) == 1
     assert L.rekv_attention_indexed(None, None, None, None, 1, None, 1, 1, None, None, None, 1, 1, 1, 1, None, None) == 1
     assert L.rekv_offload_kv(None, None, None, None, None, 0, 1, None) == 1
     assert L.rekv_offload_wait(None) == 1
