@@ -125,7 +125,7 @@ rekv_status rekv_frame_keys(rekv_ctx* ctx, const void* k, int32_t n_frames, floa
  *                       order; entries past n_sel are -1
  *   n_sel               [n_questions] int32: min(k, n_frames); may be NULL
  *   scores              [n_questions, n_frames] fp32, may be NULL
- * Limits: 1 <= k <= 4096, n_frames >= 1.
+ * Limits: 1 <= k <= 4096, n_frames >= 1, (Hq / Hkv) * D <= 4096; q_question 16-byte aligned.
  */
 rekv_status rekv_retrieve_topk(rekv_ctx* ctx, const float* frame_keys, int64_t frame_keys_stride,
                                int32_t n_frames, const void* q_question, int32_t n_questions,
@@ -139,7 +139,7 @@ rekv_status rekv_retrieve_topk(rekv_ctx* ctx, const float* frame_keys, int64_t f
  *   Sim(v, q) = v.q / (tau |v| |q|); a zero-norm vector scores 0; selection as in
  *   rekv_retrieve_topk (ties to the lower index, ascending output, -1 padding).
  *
- *   frame_emb  [n_frames, dim] fp32, 16-byte aligned, dim a multiple of 4 (<= 12284), one
+ *   frame_emb  [n_frames, dim] fp32, 16-byte aligned, dim a multiple of 4, one
  *              table shared by all questions
  *   q_emb      [n_questions, dim] fp32, 16-byte aligned
  *   tau        > 0 (a positive tau does not change the ranking, only the reported scores)
@@ -199,6 +199,22 @@ rekv_status rekv_expand_blocks(rekv_ctx* ctx, const int32_t* block_idx, int32_t 
 rekv_status rekv_gather_kv(rekv_ctx* ctx, const void* src_k, const void* src_v,
                            int32_t src_on_host, int32_t n_src_frames, const int32_t* idx,
                            int32_t n_questions, int32_t k, void* dst_k, void* dst_v, void* stream);
+
+/*
+ * rekv_gather_kv for several layers in one launch.  In the method every layer retrieves its own
+ * frames ("Internal Video KV-Cache Retrieval": retrieval runs inside each attention layer, on
+ * that layer's keys), so a whole model reloads n_layers independent selections from n_layers
+ * pairs of arenas; here they are one grid instead of n_layers small ones.
+ *
+ *   src_k, src_v  HOST arrays of n_layers device pointers, each [n_src_frames * N_f, Hkv, D]
+ *                 in HBM (1 <= n_layers <= 64); the arrays are read during the call only
+ *   idx           [n_layers, n_questions, k] int32 on the device, as in rekv_gather_kv
+ *   dst_k, dst_v  [n_layers, n_questions, k * N_f, Hkv, D] in HBM
+ * Entries of idx outside [0, n_src_frames) zero-fill their block.
+ */
+rekv_status rekv_gather_kv_layers(rekv_ctx* ctx, const void* const* src_k, const void* const* src_v,
+                                  int32_t n_layers, int32_t n_src_frames, const int32_t* idx,
+                                  int32_t n_questions, int32_t k, void* dst_k, void* dst_v, void* stream);
 
 /*
  * Reload of the retrieved KV with the position policy of the "Positional Encoding" paragraph:

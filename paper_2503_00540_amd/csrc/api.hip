@@ -337,11 +337,11 @@ rekv_status rekv_retrieve_topk(rekv_ctx* c, const float* frame_keys, int64_t fra
         return fail(c, REKV_ERR_INVALID_ARG, "rekv_retrieve_topk: n_frames=%d n_questions=%d n_q_tokens=%d k=%d (1..4096)",
                     n_frames, n_questions, n_q_tokens, k);
     const int d_prime = c->shape.n_kv_heads * c->shape.head_dim;
-    if ((size_t)(d_prime + 1) * sizeof(float) > 48 * 1024)
-        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_retrieve_topk: Hkv*D=%d exceeds 12287", d_prime);
+    if ((c->shape.n_q_heads / c->shape.n_kv_heads) * c->shape.head_dim > 4096)
+        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_retrieve_topk: (Hq/Hkv)*D=%d exceeds 4096",
+                    (c->shape.n_q_heads / c->shape.n_kv_heads) * c->shape.head_dim);
     if (n_questions > 65535) return fail(c, REKV_ERR_UNSUPPORTED, "rekv_retrieve_topk: at most 65535 questions per call");
-    const size_t qh_bytes = ((size_t)n_questions * c->shape.n_q_heads * c->shape.head_dim * sizeof(float) + 255) & ~size_t(255);
-    const size_t qv_bytes = qh_bytes + (((size_t)n_questions * d_prime * sizeof(float) + 255) & ~size_t(255));
+    const size_t qv_bytes = ((size_t)n_questions * d_prime * sizeof(float) + 255) & ~size_t(255);
     const size_t sc_bytes = scores ? 0 : (size_t)n_questions * n_frames * sizeof(float);
     rekv_status s = reserve(c, qv_bytes + sc_bytes);
     if (s != REKV_OK) return s;
@@ -351,8 +351,7 @@ rekv_status rekv_retrieve_topk(rekv_ctx* c, const float* frame_keys, int64_t fra
     a.n_q_heads = c->shape.n_q_heads; a.n_kv_heads = c->shape.n_kv_heads; a.head_dim = c->shape.head_dim;
     a.dtype = c->shape.dtype;
     a.idx = idx; a.n_sel = n_sel;
-    a.q_heads = static_cast<float*>(c->ws);
-    a.q_vec = reinterpret_cast<float*>(static_cast<char*>(c->ws) + qh_bytes);
+    a.q_vec = static_cast<float*>(c->ws);
     a.scores = scores ? scores : reinterpret_cast<float*>(static_cast<char*>(c->ws) + qv_bytes);
     a.q_vec_given = nullptr; a.dim = 0; a.inv_tau = 1.f;
     hipError_t e = rekv::retrieve_launch(a, static_cast<hipStream_t>(stream));
@@ -370,8 +369,6 @@ rekv_status rekv_retrieve_external(rekv_ctx* c, const float* frame_emb, int32_t 
         return fail(c, REKV_ERR_INVALID_ARG,
                     "rekv_retrieve_external: n_frames=%d n_questions=%d k=%d (1..4096) dim=%d (multiple of 4) tau=%g (> 0)",
                     n_frames, n_questions, k, dim, (double)tau);
-    if ((size_t)(dim + 1) * sizeof(float) > 48 * 1024)
-        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_retrieve_external: dim=%d exceeds 12284", dim);
     if (n_questions > 65535) return fail(c, REKV_ERR_UNSUPPORTED, "rekv_retrieve_external: at most 65535 questions per call");
     if (!scores) {
         rekv_status s = reserve(c, (size_t)n_questions * n_frames * sizeof(float));
@@ -493,6 +490,29 @@ rekv_status rekv_gather_kv(rekv_ctx* c, const void* src_k, const void* src_v, in
     if (e == hipSuccess) e = hipEventRecord(c->ev_side, c->side);
     if (e == hipSuccess) e = hipStreamWaitEvent(stream, c->ev_side, 0);
     return e == hipSuccess ? REKV_OK : fail_hip(c, "rekv_gather_kv: host copies", e);
+}
+
+rekv_status rekv_gather_kv_layers(rekv_ctx* c, const void* const* src_k, const void* const* src_v, int32_t n_layers,
+                                  int32_t n_src_frames, const int32_t* idx, int32_t n_questions, int32_t k,
+                                  void* dst_k, void* dst_v, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!src_k || !src_v || !idx || !dst_k || !dst_v) return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_layers: null pointer");
+    if (n_layers <= 0 || n_layers > rekv::MAX_GATHER_LAYERS)
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_layers: n_layers=%d (1..%d)", n_layers, rekv::MAX_GATHER_LAYERS);
+    if (!aligned16(dst_k) || !aligned16(dst_v))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_layers: pointers must be 16-byte aligned");
+    for (int i = 0; i < n_layers; ++i)
+        if (!src_k[i] || !src_v[i] || !aligned16(src_k[i]) || !aligned16(src_v[i]))
+            return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_layers: arena %d is null or not 16-byte aligned", i);
+    if (n_src_frames <= 0 || n_questions <= 0 || k <= 0)
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_layers: n_src_frames=%d n_questions=%d k=%d", n_src_frames, n_questions, k);
+    const int64_t per_layer = (int64_t)n_questions * k;
+    if (per_layer * n_layers > 0x7FFFFFFF) return fail(c, REKV_ERR_UNSUPPORTED, "rekv_gather_kv_layers: %lld blocks", (long long)(per_layer * n_layers));
+    const size_t frame_bytes = (size_t)c->shape.tokens_per_frame * c->shape.n_kv_heads * c->shape.head_dim * elem_size(c);
+    if (frame_bytes % 16 != 0) return fail(c, REKV_ERR_UNSUPPORTED, "rekv_gather_kv_layers: frame of %zu bytes is not a multiple of 16", frame_bytes);
+    hipError_t e = rekv::gather_layers_launch(src_k, src_v, n_layers, n_src_frames, idx, (int)per_layer, frame_bytes, dst_k,
+                                              dst_v, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "gather_layers launch", e);
 }
 
 rekv_status rekv_gather_kv_rope(rekv_ctx* c, const void* src_k, const void* src_v, int32_t n_src_frames,

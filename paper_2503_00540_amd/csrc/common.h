@@ -96,7 +96,6 @@ struct RetrieveArgs {
     int32_t* idx;
     int32_t* n_sel;
     float* scores;   // [n_questions, n_frames], never NULL here (workspace if the caller gave none)
-    float* q_heads;  // [n_questions, Hq * D] workspace: token means per query head
     float* q_vec;    // [n_questions, D'] workspace: pooled question vectors
     // External retrieval (Eq. 2 on given embeddings): q_question == NULL, q_vec_given holds the
     // question embeddings, dim their length; scores are divided by tau.
@@ -114,6 +113,11 @@ hipError_t expand_blocks_launch(const int32_t* block_idx, int n_questions, int k
 hipError_t gather_launch(const void* src_k, const void* src_v, int n_src_frames, const int32_t* idx,
                          int n_blocks, size_t frame_bytes, void* dst_k, void* dst_v,
                          hipStream_t stream);
+
+constexpr int MAX_GATHER_LAYERS = 64;
+hipError_t gather_layers_launch(const void* const* src_k, const void* const* src_v, int n_layers, int n_src_frames,
+                                const int32_t* idx, int blocks_per_layer, size_t frame_bytes, void* dst_k, void* dst_v,
+                                hipStream_t stream);
 
 // Position policy of the retrieved keys (gather.hip): new position of gathered token j of a
 // question = pos_offset (+ j unless is_static); cached keys carry no rotation, or (src_rotated)

@@ -39,6 +39,38 @@ __global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(
     }
 }
 
+// The same block copy for several layers in one launch (every layer retrieves its own frames from
+// its own arenas): the arenas' base pointers travel in the kernel arguments.
+struct LayerArenas {
+    const char* k[MAX_GATHER_LAYERS];
+    const char* v[MAX_GATHER_LAYERS];
+};
+
+__global__ __launch_bounds__(GATHER_THREADS) void gather_layers_kernel(
+    LayerArenas arenas, int blocks_per_layer, int n_src_frames, const int32_t* __restrict__ idx,
+    size_t frame_bytes, char* __restrict__ dst_k, char* __restrict__ dst_v) {
+    const int64_t blk = blockIdx.x;              // over (layer, question, selected slot)
+    const int layer = (int)(blk / blocks_per_layer);
+    const int f = idx[blk];
+    const int z = blockIdx.z;                    // 0: keys, 1: values
+    const char* src = (z ? arenas.v[layer] : arenas.k[layer]) + (size_t)(f < 0 ? 0 : f) * frame_bytes;
+    char* dst = (z ? dst_v : dst_k) + (size_t)blk * frame_bytes;
+    const bool have = f >= 0 && f < n_src_frames;
+    const size_t off0 = (size_t)blockIdx.y * SLICE + (size_t)threadIdx.x * 16;
+    u32x4 v[UNROLL];
+#pragma unroll
+    for (int i = 0; i < UNROLL; ++i) {
+        const size_t off = off0 + (size_t)i * GATHER_THREADS * 16;
+        v[i] = u32x4{0u, 0u, 0u, 0u};
+        if (have && off < frame_bytes) v[i] = *reinterpret_cast<const u32x4*>(src + off);
+    }
+#pragma unroll
+    for (int i = 0; i < UNROLL; ++i) {
+        const size_t off = off0 + (size_t)i * GATHER_THREADS * 16;
+        if (off < frame_bytes) __builtin_nontemporal_store(v[i], reinterpret_cast<u32x4*>(dst + off));
+    }
+}
+
 // Keys of the selected frames, turned to their positions in the question-answering context.
 // A unit of work is one (token, KV head, column chunk c): the 16-byte chunk at dims
 // [c*EPC, (c+1)*EPC) and its partner at + D/2, which hold both members of EPC rotary pairs
@@ -161,6 +193,20 @@ hipError_t gather_rope_launch(const void* src_k, const void* src_v, int n_src_fr
         hipLaunchKernelGGL(gather_rope_kernel<false>, kgrid, dim3(GATHER_THREADS), 0, stream,
                            static_cast<const char*>(src_k), n_src_frames, idx, k_slots, n_f, n_kv_heads, d,
                            static_cast<char*>(dst_k), ra);
+    return hipGetLastError();
+}
+
+hipError_t gather_layers_launch(const void* const* src_k, const void* const* src_v, int n_layers, int n_src_frames,
+                                const int32_t* idx, int blocks_per_layer, size_t frame_bytes, void* dst_k, void* dst_v,
+                                hipStream_t stream) {
+    LayerArenas arenas;
+    for (int i = 0; i < MAX_GATHER_LAYERS; ++i) {
+        arenas.k[i] = static_cast<const char*>(src_k[i < n_layers ? i : 0]);
+        arenas.v[i] = static_cast<const char*>(src_v[i < n_layers ? i : 0]);
+    }
+    dim3 grid((unsigned)(n_layers * blocks_per_layer), (unsigned)((frame_bytes + SLICE - 1) / SLICE), 2);
+    hipLaunchKernelGGL(gather_layers_kernel, grid, dim3(GATHER_THREADS), 0, stream, arenas, blocks_per_layer,
+                       n_src_frames, idx, frame_bytes, static_cast<char*>(dst_k), static_cast<char*>(dst_v));
     return hipGetLastError();
 }
 

@@ -8,6 +8,13 @@ namespace rekv {
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// 16-byte load that is not kept in the caches (a table row is read once per pass)
+__device__ inline float4 load_stream(const float* p) {
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
 
 __device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
@@ -78,28 +85,75 @@ __global__ __launch_bounds__(256) void frame_keys_kernel(const void* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------
-// Question vector and Eq. 2.  The token mean of a question's queries, per query head, comes
-// from the same column-mean kernel as the frame vectors (the question is a "frame" of N_q
-// rows of Hq*D columns); a small kernel then averages the G query heads of each KV group.
-// The score kernel stages the question vectors in LDS.  A wavefront then takes FR frames x
-// QBT questions at a time: every lane accumulates the FR*QBT partial dot
-// products (and the FR partial |v|^2) over its slice of the D' columns, and a transposing
-// butterfly leaves each total in one lane with one shuffle per total instead of six.
-// grid = (frame-group blocks, question blocks); wavefronts stride over the frame groups.
+// Question vector (the mean of the question's N_q query vectors; the G query heads of a KV
+// group averaged so that the vector has D' = Hkv * D entries, like a frame vector).
+// One workgroup per (question, KV group): its columns are the G * D contiguous elements of
+// that group in every token row.  16-byte loads, fp32 sums, the row groups' partial sums and
+// then the G heads meet in LDS.
 // ---------------------------------------------------------------------------------------
-constexpr int SCORE_WAVES = 4;
+constexpr int POOL_MAX_COLS = 4096;            // G * D per KV group that fits the LDS buffer
 
-// q_vec[q][g*D + dd] = mean over the G heads of group g of q_heads[q][(g*G + i)*D + dd]
-__global__ __launch_bounds__(256) void group_mean_kernel(const float* __restrict__ q_heads, int hq, int hkv,
-                                                         int d, float* __restrict__ q_vec) {
-    const int d_prime = hkv * d, g_sz = hq / hkv;
-    const int c = blockIdx.y * 256 + threadIdx.x;
-    if (c >= d_prime) return;
-    const int g = c / d, dd = c - g * d;
-    const float* src = q_heads + ((int64_t)blockIdx.x * hq + g * g_sz) * d + dd;
-    float acc = 0.f;
-    for (int j = 0; j < g_sz; ++j) acc += src[j * d];
-    q_vec[(int64_t)blockIdx.x * d_prime + c] = acc / (float)g_sz;
+template <bool BF16>
+__global__ __launch_bounds__(256) void pool_question_kernel(const void* __restrict__ q, int n_q_tokens, int hq,
+                                                            int hkv, int d, float* __restrict__ q_vec) {
+    constexpr int VEC = BF16 ? 8 : 4;
+    constexpr int ES = BF16 ? 2 : 4;
+    __shared__ float red[256 * VEC];
+    __shared__ float colsum[POOL_MAX_COLS];
+    const int g_sz = hq / hkv, cols = g_sz * d;
+    const int lpr = cols / VEC;                      // 16-byte lanes per row of this group's columns
+    const int lw = lpr < 256 ? lpr : 256;            // lanes working on a row at a time
+    const int n_rg = 256 / lw;                       // row groups
+    const int cl = threadIdx.x % lw, rg = threadIdx.x / lw;
+    const int64_t pitch = (int64_t)hq * d * ES;
+    const char* base = static_cast<const char*>(q) + (int64_t)blockIdx.x * n_q_tokens * pitch +
+                       (int64_t)blockIdx.y * cols * ES;
+    for (int c0 = 0; c0 < lpr; c0 += lw) {
+        float acc[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+        const bool on = rg < n_rg && c0 + cl < lpr;
+        if (on) {
+            const char* col = base + (int64_t)(c0 + cl) * 16;
+            constexpr int U = 16;
+            auto add = [&](const u32x4& w) {
+                if (BF16) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        acc[2 * i] += bf16_lo(w[i]);
+                        acc[2 * i + 1] += bf16_hi(w[i]);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[i] += __uint_as_float(w[i]);
+                }
+            };
+            int j = rg;
+            for (; j + n_rg * (U - 1) < n_q_tokens; j += n_rg * U) {
+                u32x4 w[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) w[u] = *reinterpret_cast<const u32x4*>(col + (j + n_rg * u) * pitch);
+#pragma unroll
+                for (int u = 0; u < U; ++u) add(w[u]);
+            }
+            for (; j < n_q_tokens; j += n_rg) add(*reinterpret_cast<const u32x4*>(col + j * pitch));
+        }
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) red[threadIdx.x * VEC + i] = acc[i];
+        __syncthreads();
+        for (int c = threadIdx.x; c < lw * VEC; c += 256) {
+            float sum = 0.f;
+            for (int g = 0; g < n_rg; ++g) sum += red[(g * lw) * VEC + c];
+            if (c0 * VEC + c < cols) colsum[c0 * VEC + c] = sum;
+        }
+        __syncthreads();
+    }
+    const float inv = 1.f / ((float)g_sz * (float)n_q_tokens);
+    for (int dd = threadIdx.x; dd < d; dd += 256) {
+        float sum = 0.f;
+        for (int g = 0; g < g_sz; ++g) sum += colsum[g * d + dd];
+        q_vec[(int64_t)blockIdx.x * hkv * d + (int64_t)blockIdx.y * d + dd] = sum * inv;
+    }
 }
 
 // Sums v[i] over the 64 lanes for all i at once.  Returns, in every lane, the total of the
@@ -306,6 +360,124 @@ __device__ inline void topk_block(const float* s, int n_frames, int k, int32_t* 
     if (tid == 0 && n_sel_q) *n_sel_q = k;
 }
 
+// ---------------------------------------------------------------------------------------
+// Top-k for the common sizes (257..4096 frames, k <= 64) without a radix select: few phases,
+// each one pass over registers or a short LDS list.
+//   1. 1024 threads hold up to 4 keys each; frame f belongs to group f mod 128, so all of a
+//      thread's keys are in group (thread mod 128) and every group is non-empty.
+//   2. The 128 group maxima are 128 different frames, so the k-th largest of them, T0, is a lower
+//      bound of the k-th largest key overall: every frame of the answer has key >= T0.
+//      Typically fewer than 2k frames pass that test.
+//   3. The survivors are ranked among themselves by (key descending, frame ascending) - all
+//      pairs, spread over the 1024 threads - and those of rank < k are the answer, exactly,
+//      ties going to the lower frame.  One wavefront puts them in ascending frame order.
+// Many equal keys at the cut only make the survivor list longer (all-pairs work grows with
+// its square), never wrong.  One workgroup per question.
+// ---------------------------------------------------------------------------------------
+constexpr int SEL_GROUPS = 128;
+constexpr int SEL_MAX_FRAMES = 4096;
+constexpr int SEL_MAX_K = 64;
+constexpr int SEL_MIN_FRAMES = 257;
+
+template <int SEL_THREADS>      // a multiple of 128 that divides 4096
+__global__ __launch_bounds__(SEL_THREADS) void topk_groupmax_kernel(const float* __restrict__ scores,
+                                                                   int n_frames, int k,
+                                                                   int32_t* __restrict__ idx,
+                                                                   int32_t* __restrict__ n_sel) {
+    // a candidate is one 64-bit word: key in the high half, ~frame in the low half, so that a
+    // larger word means "ranks before" (higher key, or equal key and lower frame)
+    __shared__ uint32_t gmax[SEL_GROUPS];
+    __shared__ __attribute__((aligned(16))) uint64_t cand[SEL_MAX_FRAMES];
+    __shared__ int32_t rank_of[SEL_MAX_FRAMES];
+    __shared__ int32_t sel[SEL_MAX_K];
+    __shared__ uint32_t sh_t0;
+    __shared__ int32_t n_cand, n_taken;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int64_t qi = blockIdx.x;
+    const float* s = scores + qi * n_frames;
+    int32_t* out = idx + qi * k;
+
+    constexpr int KPT = SEL_MAX_FRAMES / SEL_THREADS;      // keys per thread
+    uint32_t key[KPT];
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const int f = tid + j * SEL_THREADS;
+        key[j] = f < n_frames ? order_key(s[f]) : 0u;        // 0 lies below the key of every number
+    }
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) rank_of[tid + j * SEL_THREADS] = 0;
+    if (tid < SEL_GROUPS) gmax[tid] = 0u;
+    if (tid == 0) { n_cand = 0; n_taken = 0; }
+    __syncthreads();
+    uint32_t mine = key[0];
+#pragma unroll
+    for (int j = 1; j < KPT; ++j) mine = max(mine, key[j]);
+    atomicMax(&gmax[tid & (SEL_GROUPS - 1)], mine);          // tid mod 128 == the group of all its keys
+    __syncthreads();
+    if (tid < SEL_GROUPS) {
+        const uint32_t v = gmax[tid];
+        int above = 0;
+#pragma unroll 16
+        for (int j = 0; j < SEL_GROUPS; ++j) {
+            const uint32_t o = gmax[j];                      // same address in every lane: a broadcast
+            above += (o > v) || (o == v && j < tid);
+        }
+        if (above == k - 1) sh_t0 = v;
+    }
+    __syncthreads();
+    const uint32_t t0 = sh_t0;
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const int f = tid + j * SEL_THREADS;
+        const bool pass = f < n_frames && key[j] >= t0;
+        const uint64_t mask = __builtin_amdgcn_ballot_w64(pass);
+        if (mask != 0) {                                     // wave-uniform
+            int base = 0;
+            if (lane == 0) base = atomicAdd(&n_cand, __popcll(mask));
+            base = __builtin_amdgcn_readfirstlane(base);
+            if (pass) {
+                const int slot = base + __popcll(mask & ((1ull << lane) - 1ull));
+                cand[slot] = ((uint64_t)key[j] << 32) | (uint32_t)~f;
+            }
+        }
+    }
+    __syncthreads();
+    const int n = n_cand;                                    // k <= n <= n_frames
+    // all pairs: candidate i against the candidates of slice sl; a wavefront's lanes share the slice
+    const int n_up = (n + 63) & ~63;
+    const int n_slices = n_up < SEL_THREADS ? SEL_THREADS / n_up : 1;
+    const int sl = __builtin_amdgcn_readfirstlane(tid / n_up);
+    if (sl < n_slices) {
+        const int j0 = (int)((int64_t)n * sl / n_slices), j1 = (int)((int64_t)n * (sl + 1) / n_slices);
+        for (int i = tid - sl * n_up; i < n; i += SEL_THREADS) {
+            const uint64_t ci = cand[i];
+            int above = 0;
+            int j = j0;
+            for (; j + 8 <= j1; j += 8) {
+                uint64_t c[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) c[u] = cand[j + u];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) above += c[u] > ci;
+            }
+            for (; j < j1; ++j) above += cand[j] > ci;
+            if (n_slices > 1) atomicAdd(&rank_of[i], above);
+            else rank_of[i] = above;
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < n; i += SEL_THREADS)
+        if (rank_of[i] < k) sel[atomicAdd(&n_taken, 1)] = (int32_t)~(uint32_t)cand[i];    // exactly k of them
+    __syncthreads();
+    if (tid < k) {
+        const int32_t f = sel[tid];
+        int before = 0;
+        for (int j = 0; j < k; ++j) before += sel[j] < f;
+        out[before] = f;
+    }
+    if (tid == 0 && n_sel) n_sel[qi] = k;
+}
+
 __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float* __restrict__ scores,
                                                             int n_frames, int k,
                                                             int32_t* __restrict__ idx,
@@ -315,85 +487,185 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float* __restr
 }
 
 
-// For the single-question score kernel: the per-head token means it averages into the question
-// vector itself (NULL: q_vec is given), which saves the group-mean launch.
-struct QuestionHeads {
-    const float* q_heads;   // [n_questions, Hq * D] or NULL
-    int hq, hkv, d;
-};
+// ---------------------------------------------------------------------------------------
+// Eq. 2, one question per pass over a table (a question with its own table, or few questions
+// on a shared one): a wavefront takes FR frame rows at a time, the lanes split the D' columns,
+// 16-byte loads of the rows and of the question vector are all issued before the first use,
+// and a transposing butterfly leaves each row's dot product and squared norm in one lane.
+// grid = (frame groups, questions).
+// ---------------------------------------------------------------------------------------
+constexpr int SCORE_WAVES = 4;
+constexpr int SCORE_FR = 8;
 
-template <int FR, int QBT, bool POOL>
-__global__ __launch_bounds__(SCORE_WAVES * 64) void score_kernel(
+// NI > 0: D' <= NI * 256 and the column loop is unrolled NI times, so that all of a row group's
+// loads are in flight at once; NI = 0: any D'.
+template <int NI>
+__global__ __launch_bounds__(SCORE_WAVES * 64) void score_rows_kernel(
     const float* __restrict__ frame_keys, int64_t fk_stride, int n_frames, int d_prime,
-    const float* __restrict__ q_vec, int n_questions, float inv_tau, float* __restrict__ scores, QuestionHeads ft) {
-    static_assert(!POOL || QBT == 1, "in-kernel group mean serves one question per block");
-    static_assert(FR * QBT <= 64 && (FR & (FR - 1)) == 0 && (QBT & (QBT - 1)) == 0, "butterfly sizes");
-    extern __shared__ float qs[];            // [QBT][d_prime] then [QBT] squared norms
+    const float* __restrict__ q_vec, float inv_tau, float* __restrict__ scores) {
+    constexpr int FR = SCORE_FR;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int q0 = blockIdx.y * QBT;
-    const int nq_here = n_questions - q0 < QBT ? n_questions - q0 : QBT;
-    float* qn = qs + QBT * d_prime;
-    if (POOL && ft.q_heads) {
-        // the question vector: mean of the G query heads of each KV group (same order of sums as
-        // group_mean_kernel)
-        const int g_sz = ft.hq / ft.hkv;
-        for (int i = threadIdx.x; i < d_prime; i += blockDim.x) {
-            const int g = i / ft.d, dd = i - g * ft.d;
-            const float* src = ft.q_heads + ((int64_t)q0 * ft.hq + g * g_sz) * ft.d + dd;
-            float acc = 0.f;
-            for (int j = 0; j < g_sz; ++j) acc += src[j * ft.d];
-            qs[i] = acc / (float)g_sz;
-        }
-    } else {
-        for (int i = threadIdx.x; i < QBT * d_prime; i += blockDim.x)     // absent questions stay zero
-            qs[i] = i < nq_here * d_prime ? q_vec[(int64_t)q0 * d_prime + i] : 0.f;
-    }
-    __syncthreads();
-    for (int w = wave; w < QBT; w += SCORE_WAVES) {
-        float s = 0.f;
-        for (int i = lane; i < d_prime; i += 64) s += qs[w * d_prime + i] * qs[w * d_prime + i];
-        s = wave_sum(s);
-        if (lane == 0) qn[w] = s;
-    }
-    __syncthreads();
-    const float* table = frame_keys + (int64_t)q0 * fk_stride;
-    constexpr int LOG_N = __builtin_ctz(FR * QBT), LOG_FR = __builtin_ctz(FR);
+    const int qi = blockIdx.y;
+    const float* table = frame_keys + (int64_t)qi * fk_stride;
+    const float* qv = q_vec + (int64_t)qi * d_prime;
     for (int f0 = (blockIdx.x * SCORE_WAVES + wave) * FR; f0 < n_frames; f0 += gridDim.x * SCORE_WAVES * FR) {
-        float acc[FR * QBT], vv[FR];
+        float acc[FR], vv[FR], qq = 0.f;
 #pragma unroll
-        for (int i = 0; i < FR * QBT; ++i) acc[i] = 0.f;
-#pragma unroll
-        for (int i = 0; i < FR; ++i) vv[i] = 0.f;
+        for (int i = 0; i < FR; ++i) acc[i] = vv[i] = 0.f;
         const float* vrow[FR];
 #pragma unroll
         for (int fr = 0; fr < FR; ++fr) {
             const int f = f0 + fr < n_frames ? f0 + fr : n_frames - 1;   // tail: re-read the last frame
             vrow[fr] = table + (int64_t)f * d_prime;
         }
-        for (int i = lane * 4; i < d_prime; i += 256) {
-            float4 x[FR];
+        auto fold = [&](const float4 (&x)[FR], const float4& y) {
+            qq += y.x * y.x + y.y * y.y + y.z * y.z + y.w * y.w;
 #pragma unroll
             for (int fr = 0; fr < FR; ++fr) {
-                x[fr] = *reinterpret_cast<const float4*>(vrow[fr] + i);
                 vv[fr] += x[fr].x * x[fr].x + x[fr].y * x[fr].y + x[fr].z * x[fr].z + x[fr].w * x[fr].w;
+                acc[fr] += x[fr].x * y.x + x[fr].y * y.y + x[fr].z * y.z + x[fr].w * y.w;
+            }
+        };
+        if (NI > 0) {
+            float4 x[NI > 0 ? NI : 1][FR], y[NI > 0 ? NI : 1];
+#pragma unroll
+            for (int it = 0; it < NI; ++it) {
+                const int i = lane * 4 + it * 256;
+                const bool on = i < d_prime;
+                y[it] = on ? *reinterpret_cast<const float4*>(qv + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int fr = 0; fr < FR; ++fr) x[it][fr] = on ? load_stream(vrow[fr] + i) : make_float4(0.f, 0.f, 0.f, 0.f);
             }
 #pragma unroll
-            for (int w = 0; w < QBT; ++w) {
-                const float4 y = *reinterpret_cast<const float4*>(qs + w * d_prime + i);
+            for (int it = 0; it < NI; ++it) fold(x[it], y[it]);
+        } else {
+            for (int i = lane * 4; i < d_prime; i += 256) {
+                float4 x[FR];
 #pragma unroll
-                for (int fr = 0; fr < FR; ++fr)
-                    acc[fr * QBT + w] += x[fr].x * y.x + x[fr].y * y.y + x[fr].z * y.z + x[fr].w * y.w;
+                for (int fr = 0; fr < FR; ++fr) x[fr] = load_stream(vrow[fr] + i);
+                fold(x, *reinterpret_cast<const float4*>(qv + i));
             }
         }
-        const float dsum = transpose_reduce<FR * QBT>(acc, lane);
+        const float dsum = transpose_reduce<FR>(acc, lane);
         const float vsum = transpose_reduce<FR>(vv, lane);
-        const int idx = lane >> (6 - LOG_N);                 // = fr * QBT + w
-        const int fr = lane >> (6 - LOG_FR), w = idx & (QBT - 1);
-        const bool writer = (lane & ((1 << (6 - LOG_N)) - 1)) == 0;
-        if (writer && f0 + fr < n_frames && w < nq_here) {
-            const float den = sqrtf(vsum) * sqrtf(qn[w]);
-            scores[(int64_t)(q0 + w) * n_frames + f0 + fr] = den > 0.f ? dsum / den * inv_tau : 0.f;
+        qq = wave_sum(qq);
+        const int fr = lane >> 3;
+        if ((lane & 7) == 0 && f0 + fr < n_frames) {
+            const float den = sqrtf(vsum) * sqrtf(qq);
+            scores[(int64_t)qi * n_frames + f0 + fr] = den > 0.f ? dsum / den * inv_tau : 0.f;
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Eq. 2, many questions on one table: a skinny fp32 matrix product, still bound by the table's
+// bytes.  A workgroup owns a tile of 32 frames x 32 questions.  Slabs of 128 columns of the
+// table rows and of the question vectors are staged in LDS with row-contiguous loads (the next
+// slab travels into registers while the current one is used); its 8 wavefronts each take 16
+// of the slab's columns and run fp32 MFMAs (v_mfma_f32_32x32x2_f32: full fp32 products, fp32
+// sums) on operands read with one 16-byte LDS read per four MFMAs: lane (r, h) holds 4
+// consecutive columns of frame r (and of question r), h choosing which 4 of a group of 8.
+// Rows are padded by 4 floats, so the 16 lanes of a quarter-wave read 16 different bank
+// groups.  The squared norms come from the same registers; the eight partial tiles meet in
+// LDS.  The table is read once per 32 questions.  grid = (frame tiles, question tiles).
+// ---------------------------------------------------------------------------------------
+constexpr int SM_WAVES = 8, SM_TILE = 32, SM_COLS = 128, SM_PITCH = SM_COLS + 4;
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(SM_WAVES * 64) void score_shared_mfma_kernel(
+    const float* __restrict__ table, int n_frames, int d_prime, const float* __restrict__ q_vec,
+    int n_questions, float inv_tau, float* __restrict__ scores) {
+    // the staging tiles and the partial results share storage: the partials are written after the last slab
+    constexpr int STAGE_FLOATS = 2 * SM_TILE * SM_PITCH, PART_FLOATS = SM_WAVES * 16 * 64;
+    __shared__ __attribute__((aligned(16))) float lds[STAGE_FLOATS > PART_FLOATS ? STAGE_FLOATS : PART_FLOATS];
+    __shared__ float vpart[SM_WAVES][64], qpart[SM_WAVES][64];
+    float* tile_a = lds;
+    float* tile_b = lds + SM_TILE * SM_PITCH;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 31, h = lane >> 5;
+    const int f0 = blockIdx.x * SM_TILE, q0 = blockIdx.y * SM_TILE;
+    // staging: thread t moves float4 number t and t + 512 of each 32 x 32-float4 slab; DEPTH slabs are
+    // in flight from memory to registers, because one slab's MFMAs are far shorter than a memory round trip
+    constexpr int PER = SM_TILE * (SM_COLS / 4) / (SM_WAVES * 64);       // 2
+    constexpr int DEPTH = 4;
+    f32x4 xa[DEPTH][PER], xb[DEPTH][PER];
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    // Loads are unconditional (rows and columns past the end are clamped to valid ones, their
+    // values replaced by zero or never stored): straight-line code, so the waits for a slab's
+    // loads leave the later slabs' loads in flight.
+    auto fetch = [&](f32x4 (&ra)[PER], f32x4 (&rb)[PER], int c0) {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int i = threadIdx.x + u * SM_WAVES * 64;
+            const int row = i / (SM_COLS / 4);
+            int col = c0 + (i % (SM_COLS / 4)) * 4;
+            col = col < d_prime ? col : 0;                                  // D' is a multiple of 4
+            const int fr = f0 + row < n_frames ? f0 + row : n_frames - 1;
+            const int qr = q0 + row < n_questions ? q0 + row : n_questions - 1;
+            ra[u] = *reinterpret_cast<const f32x4*>(table + (int64_t)fr * d_prime + col);
+            rb[u] = *reinterpret_cast<const f32x4*>(q_vec + (int64_t)qr * d_prime + col);
+        }
+    };
+    f32x16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+    float vv = 0.f, qq = 0.f;
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) fetch(xa[d], xb[d], d * SM_COLS);
+    // Whole rounds of DEPTH slabs, no branch inside a round: slabs past D' are fetched from
+    // clamped columns and enter the tiles as zeros.
+    const int n_rounds = (d_prime + DEPTH * SM_COLS - 1) / (DEPTH * SM_COLS);
+    for (int round = 0; round < n_rounds; ++round) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            const int cc = (round * DEPTH + d) * SM_COLS;
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                const int i = threadIdx.x + u * SM_WAVES * 64;
+                const int off = (i / (SM_COLS / 4)) * SM_PITCH + (i % (SM_COLS / 4)) * 4;
+                const bool on = cc + (i % (SM_COLS / 4)) * 4 < d_prime;   // columns past D' count as zero
+                *reinterpret_cast<f32x4*>(tile_a + off) = on ? xa[d][u] : zero;
+                *reinterpret_cast<f32x4*>(tile_b + off) = on ? xb[d][u] : zero;
+            }
+            __syncthreads();
+            fetch(xa[d], xb[d], cc + DEPTH * SM_COLS);
+#pragma unroll
+            for (int g = 0; g < SM_COLS / 8 / SM_WAVES; ++g) {           // this wave's groups of 8 columns
+                const int off = r * SM_PITCH + (wave * (SM_COLS / 8 / SM_WAVES) + g) * 8 + 4 * h;
+                const f32x4 a = *reinterpret_cast<const f32x4*>(tile_a + off);
+                const f32x4 b = *reinterpret_cast<const f32x4*>(tile_b + off);
+                vv += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+                qq += b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], b[j], acc[j], 0, 0, 0);
+            }
+            __syncthreads();
+        }
+    }
+    float* part = lds;                               // [wave][16][64]
+#pragma unroll
+    for (int j = 0; j < 16; ++j) part[(wave * 16 + j) * 64 + lane] = (acc[0][j] + acc[1][j]) + (acc[2][j] + acc[3][j]);
+    vpart[wave][lane] = vv;
+    qpart[wave][lane] = qq;
+    __syncthreads();
+    // element (frame fl, question ql) of the tile sits in lane ql + 32 * ((fl / 4) % 2), register
+    // (fl / 8) * 4 + fl % 4 of every wave's accumulator
+    for (int e = threadIdx.x; e < SM_TILE * SM_TILE; e += SM_WAVES * 64) {
+        const int fl = e & 31, ql = e >> 5;
+        if (f0 + fl >= n_frames || q0 + ql >= n_questions) continue;
+        const int l = ql + 32 * ((fl >> 2) & 1), j = (fl >> 3) * 4 + (fl & 3);
+        float dot = 0.f, v2 = 0.f, q2 = 0.f;
+#pragma unroll
+        for (int w = 0; w < SM_WAVES; ++w) {
+            dot += part[(w * 16 + j) * 64 + l];
+            v2 += vpart[w][fl] + vpart[w][fl + 32];
+            q2 += qpart[w][ql] + qpart[w][ql + 32];
+        }
+        const float den = sqrtf(v2) * sqrtf(q2);
+        scores[(int64_t)(q0 + ql) * n_frames + f0 + fl] = den > 0.f ? dot / den * inv_tau : 0.f;
     }
 }
 
@@ -469,44 +741,44 @@ hipError_t expand_blocks_launch(const int32_t* block_idx, int n_questions, int k
 
 hipError_t retrieve_launch(const RetrieveArgs& a, hipStream_t stream) {
     const int d_prime = a.dim > 0 ? a.dim : a.n_kv_heads * a.head_dim;
-    // Many questions on one table: 8 frames x 8 questions per wavefront (if 8 question vectors
-    // fit 48 KB of LDS), after a group-mean launch.  Otherwise one question per block row, 4 frames
-    // per wavefront, and the kernel averages the query heads itself.
-    const bool batched = a.frame_keys_stride == 0 && a.n_questions > 1 &&
-                         (size_t)8 * (d_prime + 1) * sizeof(float) <= 48 * 1024;
     const float* q_vec = a.q_vec_given;
     hipError_t e = hipSuccess;
-    if (!q_vec) {
-        // token mean per query head: [n_questions, Hq * D] fp32
-        e = frame_keys_launch(a.q_question, a.n_questions, a.n_q_tokens, a.n_q_heads * a.head_dim,
-                              a.dtype, a.q_heads, stream);
+    if (!q_vec) {                      // pooled question vectors: [n_questions, D']
+        dim3 grid((unsigned)a.n_questions, (unsigned)a.n_kv_heads);
+        if (a.dtype == REKV_BF16)
+            hipLaunchKernelGGL(pool_question_kernel<true>, grid, dim3(256), 0, stream, a.q_question, a.n_q_tokens,
+                               a.n_q_heads, a.n_kv_heads, a.head_dim, a.q_vec);
+        else
+            hipLaunchKernelGGL(pool_question_kernel<false>, grid, dim3(256), 0, stream, a.q_question, a.n_q_tokens,
+                               a.n_q_heads, a.n_kv_heads, a.head_dim, a.q_vec);
+        e = hipGetLastError();
         if (e != hipSuccess) return e;
-        if (batched) {                 // then the group mean: [n_questions, D']
-            hipLaunchKernelGGL(group_mean_kernel, dim3((unsigned)a.n_questions, (unsigned)((d_prime + 255) / 256)),
-                               dim3(256), 0, stream, a.q_heads, a.n_q_heads, a.n_kv_heads, a.head_dim, a.q_vec);
-            e = hipGetLastError();
-            if (e != hipSuccess) return e;
-            q_vec = a.q_vec;
-        }
+        q_vec = a.q_vec;
     }
-    const int fr = batched ? 8 : 4, qbt = batched ? 8 : 1;
-    int fblocks = (a.n_frames + SCORE_WAVES * fr - 1) / (SCORE_WAVES * fr);
-    if (fblocks > 4096) fblocks = 4096;
-    dim3 sg((unsigned)fblocks, (unsigned)((a.n_questions + qbt - 1) / qbt));
-    const size_t lds = (size_t)qbt * (d_prime + 1) * sizeof(float);
-    QuestionHeads ft;
-    ft.q_heads = q_vec ? nullptr : a.q_heads;
-    ft.hq = a.n_q_heads; ft.hkv = a.n_kv_heads; ft.d = a.head_dim;
-    if (batched)
-        hipLaunchKernelGGL((score_kernel<8, 8, false>), sg, dim3(SCORE_WAVES * 64), lds, stream, a.frame_keys,
-                           a.frame_keys_stride, a.n_frames, d_prime, q_vec, a.n_questions, a.inv_tau, a.scores, ft);
-    else
-        hipLaunchKernelGGL((score_kernel<4, 1, true>), sg, dim3(SCORE_WAVES * 64), lds, stream, a.frame_keys,
-                           a.frame_keys_stride, a.n_frames, d_prime, q_vec, a.n_questions, a.inv_tau, a.scores, ft);
+    // Four or more questions on one table: the matrix-core kernel reads the table once per 32 questions.
+    // Otherwise one pass over the (question's own) table per question.
+    if (a.frame_keys_stride == 0 && a.n_questions >= 4) {
+        dim3 grid((unsigned)((a.n_frames + SM_TILE - 1) / SM_TILE), (unsigned)((a.n_questions + SM_TILE - 1) / SM_TILE));
+        hipLaunchKernelGGL(score_shared_mfma_kernel, grid, dim3(SM_WAVES * 64), 0, stream, a.frame_keys, a.n_frames,
+                           d_prime, q_vec, a.n_questions, a.inv_tau, a.scores);
+    } else {
+        int fblocks = (a.n_frames + SCORE_WAVES * SCORE_FR - 1) / (SCORE_WAVES * SCORE_FR);
+        if (fblocks > 4096) fblocks = 4096;
+        dim3 grid((unsigned)fblocks, (unsigned)a.n_questions);
+        const int ni = d_prime <= 1024 ? (d_prime + 255) / 256 : 0;
+        auto kern = ni == 1 ? score_rows_kernel<1> : ni == 2 ? score_rows_kernel<2> : ni == 3 ? score_rows_kernel<3>
+                  : ni == 4 ? score_rows_kernel<4> : score_rows_kernel<0>;
+        hipLaunchKernelGGL(kern, grid, dim3(SCORE_WAVES * 64), 0, stream, a.frame_keys,
+                           a.frame_keys_stride, a.n_frames, d_prime, q_vec, a.inv_tau, a.scores);
+    }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(topk_kernel, dim3((unsigned)a.n_questions), dim3(TOPK_THREADS), 0, stream,
-                       a.scores, a.n_frames, a.k, a.idx, a.n_sel);
+    if (a.n_frames >= SEL_MIN_FRAMES && a.n_frames <= SEL_MAX_FRAMES && a.k <= SEL_MAX_K && a.k < a.n_frames)
+        hipLaunchKernelGGL(topk_groupmax_kernel<1024>, dim3((unsigned)a.n_questions), dim3(1024), 0, stream,
+                           a.scores, a.n_frames, a.k, a.idx, a.n_sel);
+    else
+        hipLaunchKernelGGL(topk_kernel, dim3((unsigned)a.n_questions), dim3(TOPK_THREADS), 0, stream,
+                           a.scores, a.n_frames, a.k, a.idx, a.n_sel);
     return hipGetLastError();
 }
 

@@ -23,7 +23,7 @@ _DTYPES = {"f32": (REKV_F32, torch.float32), "bf16": (REKV_BF16, torch.bfloat16)
 # Every entry point include/rekv.h declares.
 SYMBOLS = ("rekv_create", "rekv_destroy", "rekv_last_error", "rekv_encode_chunk",
            "rekv_frame_keys", "rekv_retrieve_topk", "rekv_gather_kv", "rekv_qa_attention",
-           "rekv_decode_attention", "rekv_decode_attention_noalloc", "rekv_block_keys", "rekv_expand_blocks", "rekv_retrieve_external", "rekv_attention_indexed", "rekv_gather_kv_rope",
+           "rekv_decode_attention", "rekv_decode_attention_noalloc", "rekv_block_keys", "rekv_expand_blocks", "rekv_retrieve_external", "rekv_attention_indexed", "rekv_gather_kv_rope", "rekv_gather_kv_layers",
            "rekv_offload_kv", "rekv_offload_wait", "rekv_probe_copy", "rekv_probe_mfma")
 
 
@@ -76,6 +76,8 @@ def lib() -> ctypes.CDLL:
     L.rekv_attention_indexed.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_int64,
                                          c_int32, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32, c_int32,
                                          c_void_p, c_void_p]
+    L.rekv_gather_kv_layers.argtypes = [c_void_p, POINTER(c_void_p), POINTER(c_void_p), c_int32, c_int32, c_void_p,
+                                        c_int32, c_int32, c_void_p, c_void_p, c_void_p]
     L.rekv_gather_kv_rope.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_int32, c_int32, c_void_p,
                                       c_void_p, ctypes.c_double, c_int32, c_int32, c_int64, c_int32, c_int64, c_void_p]
     L.rekv_offload_kv.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32,
@@ -267,6 +269,30 @@ class Rekv:
              (self._dev(src_k, last=kh, name="src_k"), self._dev(src_v, last=kh, name="src_v"))
         self._check(self._lib.rekv_gather_kv(
             self._h, ps[0], ps[1], host_mode if on_host else 0, nf, self._dev(idx, torch.int32, name="idx"), nq, k,
+            self._dev(dst_k, name="dst_k"), self._dev(dst_v, name="dst_v"), _stream()))
+        return dst_k, dst_v
+
+    def gather_kv_layers(self, src_k: list, src_v: list, idx, n_src_frames: int | None = None, dst_k=None, dst_v=None):
+        """rekv_gather_kv_layers: src_k / src_v are lists of one device arena per layer; idx
+        [n_layers, n_questions, k] int32 on the device."""
+        kh = (self.n_kv_heads, self.head_dim)
+        n_layers = len(src_k)
+        if len(src_v) != n_layers or idx.dim() != 3 or idx.shape[0] != n_layers or idx.dtype != torch.int32:
+            raise ValueError("idx must be [n_layers, n_questions, k] int32 with one arena pair per layer")
+        nf = src_k[0].shape[0] // self.tokens_per_frame if n_src_frames is None else n_src_frames
+        for t in list(src_k) + list(src_v):
+            if t.shape[0] < nf * self.tokens_per_frame:
+                raise ValueError("an arena is shorter than n_src_frames frames")
+        _, nq, k = idx.shape
+        shape = (n_layers, nq, k * self.tokens_per_frame, *kh)
+        dst_k = torch.empty(shape, dtype=self.torch_dtype, device=idx.device) if dst_k is None else dst_k
+        dst_v = torch.empty(shape, dtype=self.torch_dtype, device=idx.device) if dst_v is None else dst_v
+        if dst_k.numel() != dst_v.numel() or dst_k.numel() != n_layers * nq * k * self.tokens_per_frame * kh[0] * kh[1]:
+            raise ValueError(f"dst_k / dst_v must hold {shape}")
+        pk = (c_void_p * n_layers)(*[self._dev(t, last=kh, name="src_k") for t in src_k])
+        pv = (c_void_p * n_layers)(*[self._dev(t, last=kh, name="src_v") for t in src_v])
+        self._check(self._lib.rekv_gather_kv_layers(
+            self._h, pk, pv, n_layers, nf, self._dev(idx, torch.int32, name="idx"), nq, k,
             self._dev(dst_k, name="dst_k"), self._dev(dst_v, name="dst_v"), _stream()))
         return dst_k, dst_v
 

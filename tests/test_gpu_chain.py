@@ -268,3 +268,34 @@ def test_offload_waits_for_the_kernel_that_writes_the_kv():
     assert torch.equal(hk[sl], src_k[sl].cpu()) and torch.equal(hv[sl], src_v[sl].cpu())
     assert not hk[:nf].any() and not hk[5 * nf:].any()      # frames outside the range were not touched
     torch.cuda.synchronize()
+
+
+# ----------------------------------------------------------------------------------------
+# per-layer gather in one launch
+# ----------------------------------------------------------------------------------------
+def test_gather_of_several_layers_in_one_launch():
+    """Three layers, each with its own K/V arenas and its own selection (one with -1 padding):
+    bit-equal to the oracle's gather layer by layer and to one rekv_gather_kv call per layer."""
+    w = W.C3.scaled(n_frames=20, n_layers=3, name="C3-gather")
+    nf = w.tokens_per_frame
+    r = Rekv.for_workload(w)
+    rng = np.random.default_rng(21)
+    ks = [W.frames_k(w, 0, w.n_frames, layer) for layer in range(3)]
+    vs = [W.frames_v(w, 0, w.n_frames, layer) for layer in range(3)]
+    dks, dvs = [dev(x, w) for x in ks], [dev(x, w) for x in vs]
+    nq, k = 2, 5
+    idx = np.stack([np.stack([np.sort(rng.choice(w.n_frames, size=k, replace=False)) for _ in range(nq)]) for _ in range(3)]).astype(np.int32)
+    idx[1, 0, 3:] = -1
+    didx = torch.from_numpy(idx).to(DEV)
+    gk, gv = r.gather_kv_layers(dks, dvs, didx, n_src_frames=w.n_frames)
+    assert gk.shape == (3, nq, k * nf, w.n_kv_heads, w.head_dim)
+    for layer in range(3):
+        one_k, one_v = r.gather_kv(dks[layer], dvs[layer], didx[layer], n_src_frames=w.n_frames)
+        assert torch.equal(gk[layer], one_k) and torch.equal(gv[layer], one_v)
+        for q in range(nq):
+            sel = [f for f in idx[layer, q] if f >= 0]
+            rk, rv = O.gather_kv(ks[layer], vs[layer], sel, nf)
+            n = len(sel) * nf
+            assert host(gk)[layer, q, :n].tobytes() == rk.astype(np.float64).tobytes()
+            assert host(gv)[layer, q, :n].tobytes() == rv.astype(np.float64).tobytes()
+            assert not host(gk)[layer, q, n:].any()
