@@ -5,7 +5,14 @@ question: sliding-window encode of every chunk (one multi-chunk launch), the fra
 retrieval (pool + cosine + top-k), the KV gather and the QA attention.  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C0..C4] [--no-cpu-baseline] [--streaming]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C0..C4] [--no-cpu-baseline]
+                    [--no-extras]
+
+After the timed steps the default run also reports, outside `value`: the same stream encoded one
+launch per chunk (`streaming_tokens_per_s`), the encode launch on all-zero inputs (what the data's
+switching activity costs in sustained clock), the bandwidth-bound kernels at the 72B-class shapes of
+C4 (`hbm_kernels`: their tables are too small at C1 to say anything about HBM), the box's own copy
+and MFMA-loop rates, and the CPU oracle on a bounded sample.  `--no-extras` leaves the first three out.
 
 The default workload is C1, the configuration the metric is quoted on; C2 (hour-long stream, KV
 offloaded to pinned host memory), C3 (28 layers) and C4 (64 concurrent questions) run the same
@@ -27,11 +34,30 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_FP32_VALU_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes of one encode launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (KiB per dispatch),
-# scaled by what the same counters read for the 1 GiB probe copy of the same run: reads x 2.0
-# (the counter prices this chip's 128-byte requests at 64 bytes), writes x 1.0.  The summary is
-# profiles/attn_bf16_encode_C1_hbm_traffic.txt
-MEASURED_TRAFFIC_BYTES = {"C1-7B-1layer": int((2.0 * 267392 + 351251) * 1024)}
+TRAFFIC_PROFILE = {"C1-7B-1layer": "profiles/attn_bf16_encode_C1_hbm_traffic.txt"}
+ENCODE_KERNEL_SOURCE = "paper_2503_00540_amd/csrc/attention_bf16.hip"
+
+
+def measured_traffic(workload_name):
+    """HBM bytes of one encode launch as the committed rocprofv3 counter summary states them
+    (FETCH_SIZE and WRITE_SIZE, calibrated on the probe copy of the same runs; written by
+    paper_2503_00540_amd/profile_summary.py).  A counter run cannot happen inside this process, so
+    the value is quoted with its source, and only while the kernel source it was measured on is
+    the one in the tree; otherwise null."""
+    import hashlib
+    import re
+    rel = TRAFFIC_PROFILE.get(workload_name)
+    if not rel or not os.path.exists(os.path.join(ROOT, rel)):
+        return None, "no counter summary for this workload under profiles/"
+    text = open(os.path.join(ROOT, rel)).read()
+    m = re.search(r"^traffic_bytes_per_launch: (\d+)$", text, re.M)
+    h = re.search(r"^kernel_source_sha256: ([0-9a-f]+)$", text, re.M)
+    if not m or not h:
+        return None, f"{rel} carries no machine-readable traffic line"
+    sha = hashlib.sha256(open(os.path.join(ROOT, ENCODE_KERNEL_SOURCE), "rb").read()).hexdigest()
+    if sha != h.group(1):
+        return None, f"{rel} was measured on another version of {ENCODE_KERNEL_SOURCE}"
+    return int(m.group(1)), f"{rel} (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this command, same kernel source)"
 
 
 def encode_flops(w) -> float:
@@ -85,6 +111,8 @@ def cpu_baseline(w, seconds_target=12.0):
     threads = max([i["num_threads"] for i in threadpool_info()] + [1])
     tokens = done * w.l_x
     return {"value": tokens / (t_enc + t_qa), "unit": "video tokens/s", "cores": threads, "kind": "oracle",
+            "cores_means": "threads of the BLAS library behind numpy's fp64 matrix products; the oracle's own "
+                           "loops over heads and chunks are serial Python",
             "sample": f"{done} steady-state chunks of {w.l_x} tokens (window {w.l_l}) encoded in "
                       f"{t_enc:.2f} s, plus frame vectors, one retrieval, gather and one QA pass over "
                       f"{n_vis} frames in {t_qa:.3f} s; fp64 numpy (BLAS threads = cores)",
@@ -182,6 +210,73 @@ def box_peaks(r, torch, copy_only=False):
     return out
 
 
+def hbm_kernels_at_c4_shapes(torch, timed_us):
+    """The bandwidth-bound kernels at the 72B-class shapes of C4 (64 questions on a 2,048-frame
+    stream; random data of the benchmark's distribution drawn on the GPU): frame vectors over the
+    stream's keys, batched retrieval, the gather of 64 x 32 frames and one decode step over the
+    gathered KV.  Algorithmic bytes, HIP-event time per call, fraction of the 8 TB/s HBM peak."""
+    from paper_2503_00540_amd import workloads as W
+    from paper_2503_00540_amd.rekv import Rekv
+    w = W.C4
+    r = Rekv.for_workload(w)
+    g = torch.Generator(device="cuda:0").manual_seed(w.seed)
+    F, nf, nq, dp = w.n_frames, w.tokens_per_frame, w.n_questions, w.d_prime
+
+    def stream():
+        out = torch.empty((F * nf, w.n_kv_heads, w.head_dim), dtype=torch.bfloat16, device="cuda:0")
+        for f in range(0, F, 256):
+            off = 0.5 * torch.randn((256, 1, w.n_kv_heads, w.head_dim), device="cuda:0", generator=g)
+            x = torch.randn((256, nf, w.n_kv_heads, w.head_dim), device="cuda:0", generator=g) + off
+            out[f * nf:(f + 256) * nf] = x.reshape(-1, w.n_kv_heads, w.head_dim).to(torch.bfloat16)
+        return out
+
+    k, v = stream(), stream()
+    fk = torch.empty((F, dp), dtype=torch.float32, device="cuda:0")
+    qq = torch.randn((nq, w.n_q_tokens, w.n_q_heads, w.head_dim), device="cuda:0", generator=g).to(torch.bfloat16)
+    gk = torch.empty((nq, w.top_k * nf, w.n_kv_heads, w.head_dim), dtype=torch.bfloat16, device="cuda:0")
+    gv = torch.empty_like(gk)
+    n_text = w.n_q_tokens + 64
+    kt = torch.randn((nq, n_text, w.n_kv_heads, w.head_dim), device="cuda:0", generator=g).to(torch.bfloat16)
+    vt = torch.randn((nq, n_text, w.n_kv_heads, w.head_dim), device="cuda:0", generator=g).to(torch.bfloat16)
+    q1 = torch.randn((nq, 1, w.n_q_heads, w.head_dim), device="cuda:0", generator=g).to(torch.bfloat16)
+    o1 = torch.empty_like(q1)
+    r.frame_keys(k, F, out=fk)
+    idx, _, _ = r.retrieve_topk(fk, F, qq, w.top_k)
+    rows = {
+        "frame_keys": (F * nf * dp * 2 + F * dp * 4, lambda: r.frame_keys(k, F, out=fk)),
+        "retrieve_pool_score_topk": (nq * w.n_q_tokens * w.n_q_heads * w.head_dim * 2 + F * dp * 4 + nq * F * 4 * 2,
+                                     lambda: r.retrieve_topk(fk, F, qq, w.top_k)),
+        "gather": (2 * 2 * nq * w.top_k * nf * dp * 2, lambda: r.gather_kv(k, v, idx, n_src_frames=F, dst_k=gk, dst_v=gv)),
+        "decode_step": (2 * nq * (w.top_k * nf + n_text) * dp * 2, lambda: r.decode_attention(q1, gk, gv, kt, vt, n_text, out=o1)),
+    }
+    out = {"shapes": f"{w.name}: {F} frames x {nf} tokens, Hq/Hkv/D {w.n_q_heads}/{w.n_kv_heads}/{w.head_dim}, "
+                     f"{nq} questions, top-k {w.top_k}; HIP-event time per call over 20 calls back to back",
+           "peak_GBs": PEAK_HBM_GBS}
+    for name, (nbytes, fn) in rows.items():
+        us = timed_us(fn)
+        out[name] = {"bytes": nbytes, "us": us, "GBs": nbytes / us / 1e3, "frac_of_hbm_peak": nbytes / us / 1e3 / PEAK_HBM_GBS}
+    out["retrieve_pool_score_topk"]["note"] = ("three dependent launches of a few us each; the bytes are the questions' "
+                                               "queries, the frame table once and the scores written and read")
+    return out
+
+
+def host_link_peak(torch, n_bytes):
+    """One pinned-host-to-HBM copy of n_bytes through the copy engine: the rate the gather from
+    offloaded KV is to be read against."""
+    src = torch.empty(n_bytes, dtype=torch.uint8, pin_memory=True)
+    src.fill_(1)
+    dst = torch.empty(n_bytes, dtype=torch.uint8, device="cuda:0")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    dst.copy_(src, non_blocking=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src, non_blocking=True)
+    e1.record()
+    torch.cuda.synchronize()
+    return 5 * n_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -189,11 +284,10 @@ def main() -> None:
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3", "C4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--streaming", action="store_true",
-                    help="also time the stream encoded one launch per chunk (extra launches in a trace)")
-    ap.add_argument("--zero-input-diagnostic", action="store_true",
-                    help="also time the encode launch on all-zero inputs (extra launches of the encode kernel in a "
-                         "trace, so not part of the default run)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="leave out the measurements after the timed steps that launch further kernels: the stream "
+                         "encoded one launch per chunk, the encode launch on all-zero inputs, the C4-shaped "
+                         "bandwidth-bound kernels")
     ap.add_argument("--probe-copy-only", action="store_true",
                     help="run only the known-size copy kernel (the calibration run of the HBM byte counters)")
     args = ap.parse_args()
@@ -265,14 +359,16 @@ def main() -> None:
             rec("offload_wait")
             r.offload_wait()
         rec("retrieve")
-        idx, _, _ = r.retrieve_topk(fk, F, d["qq"], w.top_k, frame_keys_stride=F * d_prime if L > 1 else 0)
-        for layer in range(L):
-            rec("gather")
-            src = (hk, hv) if w.kv_on_host else (d["k"][layer], d["v"][layer])
-            r.gather_kv(src[0], src[1], idx[layer * nq:(layer + 1) * nq], n_src_frames=F,
-                        dst_k=gk[layer * nq:(layer + 1) * nq], dst_v=gv[layer * nq:(layer + 1) * nq])
+        idx, n_sel, _ = r.retrieve_topk(fk, F, d["qq"], w.top_k, frame_keys_stride=F * d_prime if L > 1 else 0)
+        rec("gather")
+        if w.kv_on_host:
+            r.gather_kv(hk, hv, idx, n_src_frames=F, dst_k=gk, dst_v=gv)
+        elif L > 1:                    # every layer's selection from its own arenas, one launch
+            r.gather_kv_layers(d["k"], d["v"], idx.view(L, nq, w.top_k), n_src_frames=F, dst_k=gk, dst_v=gv)
+        else:
+            r.gather_kv(d["k"][0], d["v"][0], idx, n_src_frames=F, dst_k=gk, dst_v=gv)
         rec("qa")
-        r.qa_attention(d["qq"], gk, gv, d["qk"], d["qv"], out=qa_out)
+        r.qa_attention(d["qq"], gk, gv, d["qk"], d["qv"], out=qa_out, n_sel=n_sel)
         rec(None)
         return idx
 
@@ -305,7 +401,8 @@ def main() -> None:
 
     # the same stream encoded chunk by chunk (one launch per chunk, as a live stream arrives)
     streaming_s = None
-    if args.streaming:
+    extras = not args.no_extras
+    if extras:
         dq, dk, dv = d["q"][0], d["k"][0], d["v"][0]
         torch.cuda.synchronize()
         t1 = time.perf_counter()
@@ -364,7 +461,7 @@ def main() -> None:
     # the same encode launch on all-zero inputs: same instructions and traffic, least switching
     # power; the gap to the timed figure is what the data's toggling costs in sustained clock
     zero_tflops = None
-    if w.dtype == "bf16" and args.zero_input_diagnostic:
+    if w.dtype == "bf16" and extras:
         zq, zk = torch.zeros_like(d["q"][0]), torch.zeros_like(d["k"][0])
         zero_us = timed_us(lambda: r.encode_chunk(zq, zk, zk, 0, w.l_x, n_chunks, w.l_l, out=out), reps=5)
         zero_tflops = encode_flops(w) / zero_us / 1e6
@@ -383,6 +480,7 @@ def main() -> None:
     es = 2 if w.dtype == "bf16" else 4
     gather_bytes = 2 * L * nq * w.top_k * nf * d_prime * es          # K and V, read once (and written once)
     fk_bytes = L * (w.n_tokens * d_prime * es + F * d_prime * 4)
+    traffic, traffic_source = measured_traffic(w.name)
     result = {
         "metric": "video tokens/s encoded (windowed attn, MFMA %); retrieval+QA latency ms (HBM GB/s)",
         "value": tokens_per_s, "unit": "video tokens/s", "n_gpus": 1, "steps": steps,
@@ -398,7 +496,7 @@ def main() -> None:
         "roofline": {"bound": bound, "kernel": "attn_bf16_kernel<D, true> (rekv_encode_chunk)" if w.dtype == "bf16"
                      else "attn_f32_kernel (rekv_encode_chunk)",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                     "frac": achieved / peak, "traffic": traffic, "traffic_source": traffic_source,
                      "algorithmic_flop_per_launch": fl, "avg_launch_ms": enc_launch_ms},
         "kernel_ms": ms,
         "retrieval_qa_latency_ms": ms["retrieve"] + ms["gather"] + ms["qa"],
@@ -419,6 +517,15 @@ def main() -> None:
                             "what": "block vectors from the frame table + scores + top-k + frame list, one layer"},
         "box_peaks": dict(box_peaks(r, torch), encode_on_zero_inputs_TFLOPs=zero_tflops),
     }
+    if streaming_s:
+        result["streaming"] = {"launches": n_chunks, "wall_ms": streaming_s * 1e3, "us_per_chunk": streaming_s / n_chunks * 1e6,
+                               "what": "the same stream encoded one rekv_encode_chunk call per chunk, back to back on one stream"}
+    if w.kv_on_host:
+        result["hbm"]["host_link_pinned_copy_GBs"] = host_link_peak(torch, gather_bytes)
+        result["hbm"]["gather_frac_of_host_link"] = (result["hbm"]["gather_host_link_GBs"] /
+                                                     result["hbm"]["host_link_pinned_copy_GBs"])
+    if extras and w.dtype == "bf16":
+        result["hbm_kernels"] = hbm_kernels_at_c4_shapes(torch, timed_us)
     bp = result["box_peaks"]
     if w.dtype == "bf16" and bp.get("mfma_bf16_loop_TFLOPs"):
         bp["encode_frac_of_mfma_loop"] = achieved / bp["mfma_bf16_loop_TFLOPs"]
