@@ -229,15 +229,19 @@ rekv_status rekv_gather_kv_layers(rekv_ctx* ctx, const void* const* src_k, const
  * the difference.  rope_layout 0 pairs dims (i, i + D/2), 1 pairs dims (2i, 2i + 1).
  * Angles are formed and range-reduced in double precision.
  *
- *   src_k, src_v, idx, dst_k, dst_v, n_src_frames, n_questions, k   as in rekv_gather_kv,
- *                 source in HBM only; entries of idx outside the arena zero-fill their block
+ *   src_k, src_v, idx, dst_k, dst_v, n_src_frames, n_questions, k   as in rekv_gather_kv;
+ *                 entries of idx outside the arena zero-fill their block
+ *   src_on_host   0: the arenas are in HBM; 1: they are pinned host memory (host pointers, from
+ *                 hipHostMalloc) - offloaded KV - and the kernels read them over the host link on
+ *                 the context's side stream, ordered after `stream` and joined back into it, as
+ *                 host path 2 of rekv_gather_kv does
  *   rope_base     > 1 (10000 in RoFormer)
  *   D             a multiple of 16 (bf16) or 8 (fp32), at most 256
  */
-rekv_status rekv_gather_kv_rope(rekv_ctx* ctx, const void* src_k, const void* src_v, int32_t n_src_frames,
-                                const int32_t* idx, int32_t n_questions, int32_t k, void* dst_k, void* dst_v,
-                                double rope_base, int32_t rope_layout, int32_t pos_mode, int64_t pos_offset,
-                                int32_t src_rotated, int64_t src_pos_offset, void* stream);
+rekv_status rekv_gather_kv_rope(rekv_ctx* ctx, const void* src_k, const void* src_v, int32_t src_on_host,
+                                int32_t n_src_frames, const int32_t* idx, int32_t n_questions, int32_t k,
+                                void* dst_k, void* dst_v, double rope_base, int32_t rope_layout, int32_t pos_mode,
+                                int64_t pos_offset, int32_t src_rotated, int64_t src_pos_offset, void* stream);
 
 /*
  * Question answering over the retrieved KV, Eq. 3 with X = the question tokens: every
@@ -318,6 +322,30 @@ rekv_status rekv_attention_indexed(rekv_ctx* ctx, const void* q, const void* k_s
                                    int32_t n_ret_frames, const int32_t* n_sel, const void* k_text, const void* v_text,
                                    int64_t text_stride, int32_t n_text_tokens, int32_t n_questions,
                                    int32_t n_new_tokens, void* out, void* stream);
+
+/*
+ * rekv_attention_indexed with the position policy of the "Positional Encoding" paragraph: the
+ * retrieved frames' VALUES are read in place through the frame list, their KEYS are first turned
+ * to the positions they take in the question-answering context (a pre-pass over the frame list
+ * that writes the re-positioned keys to k_pos; values carry no position), then Eq. 3 runs on
+ * those keys.  Against gather-with-positions followed by attention this saves writing and
+ * re-reading the values.  Position arguments as in rekv_gather_kv_rope (pos_mode 0: gathered
+ * token j of a question gets position pos_offset + j; 1: pos_offset for all); attention
+ * arguments as in rekv_attention_indexed, with idx_stride == n_ret_frames.
+ *
+ *   k_pos   [n_questions, n_ret_frames * N_f, Hkv, D] in HBM, caller-owned scratch that receives
+ *           the re-positioned keys (its contents after the call are those keys; blocks of
+ *           entries outside the arena are zero)
+ *   k_src, v_src   in HBM, the V arena below 4 GiB
+ */
+rekv_status rekv_attention_indexed_rope(rekv_ctx* ctx, const void* q, const void* k_src, const void* v_src,
+                                        int32_t n_src_frames, const int32_t* idx, int64_t idx_stride,
+                                        int32_t n_ret_frames, const int32_t* n_sel, void* k_pos,
+                                        double rope_base, int32_t rope_layout, int32_t pos_mode,
+                                        int64_t pos_offset, int32_t src_rotated, int64_t src_pos_offset,
+                                        const void* k_text, const void* v_text, int64_t text_stride,
+                                        int32_t n_text_tokens, int32_t n_questions, int32_t n_new_tokens,
+                                        void* out, void* stream);
 
 /*
  * Offload of encoded KV to RAM (the paragraph after Eq. 1: every frame's KV is kept, and what

@@ -515,34 +515,117 @@ rekv_status rekv_gather_kv_layers(rekv_ctx* c, const void* const* src_k, const v
     return e == hipSuccess ? REKV_OK : fail_hip(c, "gather_layers launch", e);
 }
 
-rekv_status rekv_gather_kv_rope(rekv_ctx* c, const void* src_k, const void* src_v, int32_t n_src_frames,
-                                const int32_t* idx, int32_t n_questions, int32_t k, void* dst_k, void* dst_v,
-                                double rope_base, int32_t rope_layout, int32_t pos_mode, int64_t pos_offset,
-                                int32_t src_rotated, int64_t src_pos_offset, void* stream) {
+// Argument checks and RopeArgs shared by the calls that re-position keys.
+static rekv_status rope_args(rekv_ctx* c, const char* fn, double rope_base, int32_t rope_layout, int32_t pos_mode,
+                             int64_t pos_offset, int32_t src_rotated, int64_t src_pos_offset, rekv::RopeArgs* ra) {
+    if (!(rope_base > 1.0) || !(rope_base < 1e30) || (rope_layout != 0 && rope_layout != 1) ||
+        (pos_mode != 0 && pos_mode != 1) || (src_rotated != 0 && src_rotated != 1))
+        return fail(c, REKV_ERR_INVALID_ARG, "%s: rope_base=%g (> 1) rope_layout=%d pos_mode=%d src_rotated=%d (each 0 or 1)", fn,
+                    rope_base, rope_layout, pos_mode, src_rotated);
+    const int d = c->shape.head_dim, epc = c->shape.dtype == REKV_BF16 ? 8 : 4;
+    if (d > 256 || d % (2 * epc) != 0)
+        return fail(c, REKV_ERR_UNSUPPORTED, "%s: head_dim=%d must be a multiple of %d, at most 256", fn, d, 2 * epc);
+    const int64_t span = (int64_t)1 << 40;     // positions far below 2^53 keep the double-precision angle exact
+    if (pos_offset < -span || pos_offset > span || src_pos_offset < -span || src_pos_offset > span)
+        return fail(c, REKV_ERR_INVALID_ARG, "%s: position offsets must lie within +-2^40", fn);
+    ra->log2_base = log2(rope_base);
+    ra->pos_offset = pos_offset; ra->src_pos_offset = src_pos_offset;
+    ra->is_static = pos_mode; ra->src_rotated = src_rotated; ra->interleaved = rope_layout;
+    return REKV_OK;
+}
+
+rekv_status rekv_gather_kv_rope(rekv_ctx* c, const void* src_k, const void* src_v, int32_t src_on_host,
+                                int32_t n_src_frames, const int32_t* idx, int32_t n_questions, int32_t k,
+                                void* dst_k, void* dst_v, double rope_base, int32_t rope_layout, int32_t pos_mode,
+                                int64_t pos_offset, int32_t src_rotated, int64_t src_pos_offset, void* stream_) {
     if (!c) return REKV_ERR_INVALID_ARG;
     if (!src_k || !src_v || !idx || !dst_k || !dst_v) return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_rope: null pointer");
     if (!aligned16(src_k) || !aligned16(src_v) || !aligned16(dst_k) || !aligned16(dst_v))
         return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_rope: pointers must be 16-byte aligned");
-    if (n_src_frames <= 0 || n_questions <= 0 || k <= 0 || (int64_t)n_questions * k > 0x7FFFFFFF)
-        return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_rope: n_src_frames=%d n_questions=%d k=%d", n_src_frames, n_questions, k);
-    if (!(rope_base > 1.0) || !(rope_base < 1e30) || (rope_layout != 0 && rope_layout != 1) ||
-        (pos_mode != 0 && pos_mode != 1) || (src_rotated != 0 && src_rotated != 1))
-        return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_rope: rope_base=%g (> 1) rope_layout=%d pos_mode=%d src_rotated=%d (each 0 or 1)",
-                    rope_base, rope_layout, pos_mode, src_rotated);
-    const int d = c->shape.head_dim, epc = c->shape.dtype == REKV_BF16 ? 8 : 4;
-    if (d > 256 || d % (2 * epc) != 0)
-        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_gather_kv_rope: head_dim=%d must be a multiple of %d, at most 256", d, 2 * epc);
-    const int64_t span = (int64_t)1 << 40;     // positions far below 2^53 keep the double-precision angle exact
-    if (pos_offset < -span || pos_offset > span || src_pos_offset < -span || src_pos_offset > span)
-        return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_rope: position offsets must lie within +-2^40");
+    if (n_src_frames <= 0 || n_questions <= 0 || k <= 0 || (int64_t)n_questions * k > 0x7FFFFFFF ||
+        (src_on_host != 0 && src_on_host != 1))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_rope: n_src_frames=%d n_questions=%d k=%d src_on_host=%d (0 or 1)",
+                    n_src_frames, n_questions, k, src_on_host);
     rekv::RopeArgs ra;
-    ra.log2_base = log2(rope_base);
-    ra.pos_offset = pos_offset; ra.src_pos_offset = src_pos_offset;
-    ra.is_static = pos_mode; ra.src_rotated = src_rotated; ra.interleaved = rope_layout;
-    hipError_t e = rekv::gather_rope_launch(src_k, src_v, n_src_frames, idx, n_questions, k, c->shape.tokens_per_frame,
-                                            c->shape.n_kv_heads, d, c->shape.dtype, dst_k, dst_v, ra,
+    rekv_status st = rope_args(c, "rekv_gather_kv_rope", rope_base, rope_layout, pos_mode, pos_offset, src_rotated,
+                               src_pos_offset, &ra);
+    if (st != REKV_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (!src_on_host) {
+        hipError_t e = rekv::gather_rope_launch(src_k, src_v, n_src_frames, idx, n_questions, k, c->shape.tokens_per_frame,
+                                                c->shape.n_kv_heads, c->shape.head_dim, c->shape.dtype, dst_k, dst_v, ra, stream);
+        return e == hipSuccess ? REKV_OK : fail_hip(c, "gather_kv_rope launch", e);
+    }
+    // Pinned host source: the kernels read the host arrays over the host link, on the side stream,
+    // ordered after `stream` (which produced idx) and joined back into it.
+    void *dk = nullptr, *dv = nullptr;
+    hipError_t e = hipHostGetDevicePointer(&dk, const_cast<void*>(src_k), 0);
+    if (e == hipSuccess) e = hipHostGetDevicePointer(&dv, const_cast<void*>(src_v), 0);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_gather_kv_rope: src is not pinned host memory (%s)", hipGetErrorString(e));
+    }
+    e = hipEventRecord(c->ev_main, stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent(c->side, c->ev_main, 0);
+    if (e == hipSuccess)
+        e = rekv::gather_rope_launch(dk, dv, n_src_frames, idx, n_questions, k, c->shape.tokens_per_frame, c->shape.n_kv_heads,
+                                     c->shape.head_dim, c->shape.dtype, dst_k, dst_v, ra, c->side);
+    if (e == hipSuccess) e = hipEventRecord(c->ev_side, c->side);
+    if (e == hipSuccess) e = hipStreamWaitEvent(stream, c->ev_side, 0);
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "rekv_gather_kv_rope: host-source gather", e);
+}
+
+rekv_status rekv_attention_indexed_rope(rekv_ctx* c, const void* q, const void* k_src, const void* v_src,
+                                        int32_t n_src_frames, const int32_t* idx, int64_t idx_stride,
+                                        int32_t n_ret_frames, const int32_t* n_sel, void* k_pos, double rope_base,
+                                        int32_t rope_layout, int32_t pos_mode, int64_t pos_offset, int32_t src_rotated,
+                                        int64_t src_pos_offset, const void* k_text, const void* v_text,
+                                        int64_t text_stride, int32_t n_text_tokens, int32_t n_questions,
+                                        int32_t n_new_tokens, void* out, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    if (!q || !k_src || !v_src || !idx || !k_pos || !k_text || !v_text || !out)
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_attention_indexed_rope: null pointer");
+    if (!aligned16(q) || !aligned16(k_src) || !aligned16(v_src) || !aligned16(k_pos) || !aligned16(k_text) ||
+        !aligned16(v_text) || !aligned16(out))
+        return fail(c, REKV_ERR_INVALID_ARG, "rekv_attention_indexed_rope: pointers must be 16-byte aligned");
+    if (n_src_frames <= 0 || n_ret_frames <= 0 || idx_stride != n_ret_frames || n_questions <= 0 ||
+        n_new_tokens <= 0 || n_text_tokens < n_new_tokens || text_stride < n_text_tokens)
+        return fail(c, REKV_ERR_INVALID_ARG,
+                    "rekv_attention_indexed_rope: n_src_frames=%d n_ret_frames=%d idx_stride=%lld (must equal n_ret_frames) "
+                    "n_questions=%d n_new_tokens=%d n_text_tokens=%d text_stride=%lld", n_src_frames, n_ret_frames,
+                    (long long)idx_stride, n_questions, n_new_tokens, n_text_tokens, (long long)text_stride);
+    const int64_t n_f = c->shape.tokens_per_frame;
+    const int64_t row_bytes = (int64_t)c->shape.n_kv_heads * c->shape.head_dim * (int64_t)elem_size(c);
+    if (n_ret_frames > 1024 || n_ret_frames * n_f >= (1 << 23))
+        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_attention_indexed_rope: at most 1024 frames and 2^23 - 1 tokens per question (got %d frames)",
+                    n_ret_frames);
+    if ((int64_t)n_src_frames * n_f * row_bytes > 0xFFF00000LL)
+        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_attention_indexed_rope: the V arena must stay below 4 GiB (%d frames of %lld bytes)",
+                    n_src_frames, (long long)(n_f * row_bytes));
+    if ((int64_t)n_questions * n_ret_frames > 0x7FFFFFFF ||
+        (int64_t)n_new_tokens * (c->shape.n_q_heads / c->shape.n_kv_heads) > 0x3FFFFFFF)
+        return fail(c, REKV_ERR_UNSUPPORTED, "rekv_attention_indexed_rope: too many frames or new tokens");
+    rekv::RopeArgs ra;
+    rekv_status st = rope_args(c, "rekv_attention_indexed_rope", rope_base, rope_layout, pos_mode, pos_offset, src_rotated,
+                               src_pos_offset, &ra);
+    if (st != REKV_OK) return st;
+    // pre-pass over the index list: the selected frames' keys, turned to their new positions, into k_pos
+    hipError_t e = rekv::gather_rope_launch(k_src, v_src, n_src_frames, idx, n_questions, n_ret_frames, (int)n_f,
+                                            c->shape.n_kv_heads, c->shape.head_dim, c->shape.dtype, k_pos, nullptr, ra,
                                             static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? REKV_OK : fail_hip(c, "gather_kv_rope launch", e);
+    if (e != hipSuccess) return fail_hip(c, "rekv_attention_indexed_rope: key pre-pass", e);
+    rekv::AttnProblem p;
+    memset(&p, 0, sizeof(p));
+    p.q = q; p.out = out;
+    p.k_a = k_pos; p.v_a = v_src; p.k_b = k_text; p.v_b = v_text;
+    p.len_a = (int32_t)(n_ret_frames * n_f); p.len_b = n_text_tokens; p.len_q = n_new_tokens;
+    p.b_stride = text_stride;
+    p.n_items = n_questions; p.is_encode = 0;
+    p.n_q_heads = c->shape.n_q_heads; p.n_kv_heads = c->shape.n_kv_heads; p.head_dim = c->shape.head_dim;
+    p.scale = c->scale;
+    p.a_index = idx; p.a_index_stride = idx_stride; p.n_f = (int32_t)n_f; p.n_src_frames = n_src_frames;
+    p.a_valid_frames = n_sel; p.a_k_dense = 1;
+    return run_attention(c, p, static_cast<hipStream_t>(stream));
 }
 
 rekv_status rekv_offload_kv(rekv_ctx* c, const void* dev_k, const void* dev_v, void* host_k, void* host_v,

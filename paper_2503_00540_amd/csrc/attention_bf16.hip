@@ -171,7 +171,10 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     const ItemSegs seg = item_segments(p, item);
     const int64_t row_stride = (int64_t)p.n_kv_heads * D;
     const uint32_t row_stride_b = (uint32_t)row_stride * 2u;
-    const char* ka = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_a) + seg.a_off * row_stride + kvh * D);
+    // keys of an indexed segment A may sit in a dense per-item buffer (re-positioned copies)
+    const bool k_dense = INDEXED && p.a_k_dense;
+    const int64_t ka_off = k_dense ? (int64_t)item * p.len_a : seg.a_off;
+    const char* ka = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_a) + ka_off * row_stride + kvh * D);
     const char* va = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.v_a) + seg.a_off * row_stride + kvh * D);
     const char* kb = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_b) + seg.b_off * row_stride + kvh * D);
     const char* vb = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.v_b) + seg.b_off * row_stride + kvh * D);
@@ -273,10 +276,10 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     const char* v_run = nullptr;
     // Any tile (clamped to the last tile of this workgroup's list); a segment's ragged last
     // tile re-reads the segment's last key for the rows past its end.
-    auto dma_any = [&](const char* seg_a, const char* seg_b, int t, uint32_t stage_b) {
+    auto dma_any = [&](const char* seg_a, const char* seg_b, int t, uint32_t stage_b, bool through_index = true) {
         t = t < t_end - 1 ? t : t_end - 1;
         const bool in_b = t >= tiles_a;
-        if (INDEXED && !in_b) {
+        if (INDEXED && !in_b && through_index) {
             dma_indexed(seg_a, t, stage_b);
             return;
         }
@@ -338,7 +341,12 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
         constexpr uint32_t VC = decltype(vc)::value * TILE_B, VL = decltype(vl)::value * TILE_B;
         constexpr bool PLAIN = decltype(plain)::value;
         if (PLAIN && INDEXED) {
-            dma_indexed(ka, t + 4, KL);
+            if (k_dense) {
+                dma_fast(k_run, KL);
+                k_run += tile_stride_b;
+            } else {
+                dma_indexed(ka, t + 4, KL);
+            }
             dma_indexed(va, t + 3, STAGES * TILE_B + VL);
         } else if (PLAIN) {
             dma_fast(k_run, KL);
@@ -346,7 +354,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
             k_run += tile_stride_b;
             v_run += tile_stride_b;
         } else {
-            dma_any(ka, kb, t + 4, KL);
+            dma_any(ka, kb, t + 4, KL, !k_dense);
             dma_any(va, vb, t + 3, STAGES * TILE_B + VL);
         }
         // All LDS operand reads of this step are issued first; the running-maximum work below
@@ -437,10 +445,10 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
     if (t_begin < t_end) {
         f32x16 s_a, s_b;
         constexpr uint32_t VB = STAGES * TILE_B;
-        dma_any(ka, kb, t_begin, 0);
-        dma_any(ka, kb, t_begin + 1, TILE_B);
-        dma_any(ka, kb, t_begin + 2, 2 * TILE_B);
-        dma_any(ka, kb, t_begin + 3, 3 * TILE_B);
+        dma_any(ka, kb, t_begin, 0, !k_dense);
+        dma_any(ka, kb, t_begin + 1, TILE_B, !k_dense);
+        dma_any(ka, kb, t_begin + 2, 2 * TILE_B, !k_dense);
+        dma_any(ka, kb, t_begin + 3, 3 * TILE_B, !k_dense);
         dma_any(va, vb, t_begin, VB);
         dma_any(va, vb, t_begin + 1, VB + TILE_B);
         dma_any(va, vb, t_begin + 2, VB + 2 * TILE_B);
@@ -464,7 +472,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(KernelArgs a) {
         if (!wave_active) {
             for (; t < t_end; ++t) {           // same loads into the same stages as the steps below
                 const uint32_t i4 = (uint32_t)(t - t_begin) & 3u;
-                dma_any(ka, kb, t + 4, i4 * TILE_B);
+                dma_any(ka, kb, t + 4, i4 * TILE_B, !k_dense);
                 dma_any(va, vb, t + 3, VB + ((i4 + 3u) & 3u) * TILE_B);
                 step_barrier<2 * DMA_PER_STEP>();
             }

@@ -34,7 +34,8 @@ __global__ __launch_bounds__(ROWS_PER_BLOCK * 64) void attn_f32_kernel(AttnProbl
     const int tok = (int)(r / p.n_q_heads), h = (int)(r % p.n_q_heads), kvh = h / G;
     const ItemSegs seg = item_segments(p, item);
     const int64_t row_stride = (int64_t)p.n_kv_heads * D;
-    const float* ka = static_cast<const float*>(p.k_a) + seg.a_off * row_stride + kvh * D;
+    const bool k_dense = p.a_index && p.a_k_dense;      // re-positioned keys in a dense per-item buffer
+    const float* ka = static_cast<const float*>(p.k_a) + (k_dense ? (int64_t)item * p.len_a : seg.a_off) * row_stride + kvh * D;
     const float* va = static_cast<const float*>(p.v_a) + seg.a_off * row_stride + kvh * D;
     const float* kb = static_cast<const float*>(p.k_b) + seg.b_off * row_stride + kvh * D;
     const float* vb = static_cast<const float*>(p.v_b) + seg.b_off * row_stride + kvh * D;
@@ -61,7 +62,7 @@ __global__ __launch_bounds__(ROWS_PER_BLOCK * 64) void attn_f32_kernel(AttnProbl
         float s = -INFINITY;
         const float* vrow = nullptr;
         if (j < n_keys) {
-            const float* krow = j < seg.len_a ? ka + a_row(j) * row_stride
+            const float* krow = j < seg.len_a ? ka + (k_dense ? (int64_t)j : a_row(j)) * row_stride
                                               : kb + (int64_t)(j - seg.len_a) * row_stride;
             float acc = 0.f;
             for (int d = 0; d < D; d += 4) {

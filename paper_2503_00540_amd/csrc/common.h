@@ -43,6 +43,10 @@ struct AttnProblem {
     // QA / decode: frames actually retrieved per item (device int32 [n_items], NULL = all): item i
     // attends to the first min(a_valid_frames[i] * n_f, len_a) tokens of its segment A only.
     const int32_t* a_valid_frames;
+    // With a_index: the KEYS of segment A come from a dense per-item buffer [n_items, len_a, Hkv, D]
+    // at k_a (keys re-positioned by a pre-pass over the index list) while the values are still
+    // read in place through the index list.
+    int32_t a_k_dense;
 };
 
 // Resolves one item's segment bases (in elements) and lengths.  Device only: it reads the

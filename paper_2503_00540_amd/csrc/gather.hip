@@ -174,13 +174,15 @@ hipError_t gather_rope_launch(const void* src_k, const void* src_v, int n_src_fr
     const int n_blocks = n_questions * k_slots;
     const size_t es = dtype == REKV_BF16 ? 2 : 4;
     const size_t frame_bytes = (size_t)n_f * n_kv_heads * d * es;
-    // values: the plain block copy
-    dim3 vgrid((unsigned)n_blocks, (unsigned)((frame_bytes + SLICE - 1) / SLICE), 1);
-    hipLaunchKernelGGL(gather_kernel, vgrid, dim3(GATHER_THREADS), 0, stream, static_cast<const char*>(src_k),
-                       static_cast<const char*>(src_v), n_src_frames, idx, frame_bytes,
-                       static_cast<char*>(dst_k), static_cast<char*>(dst_v), 1);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    hipError_t e = hipSuccess;
+    if (dst_v) {                       // values: the plain block copy (skipped when only keys are wanted)
+        dim3 vgrid((unsigned)n_blocks, (unsigned)((frame_bytes + SLICE - 1) / SLICE), 1);
+        hipLaunchKernelGGL(gather_kernel, vgrid, dim3(GATHER_THREADS), 0, stream, static_cast<const char*>(src_k),
+                           static_cast<const char*>(src_v), n_src_frames, idx, frame_bytes,
+                           static_cast<char*>(dst_k), static_cast<char*>(dst_v), 1);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     const int units = n_f * n_kv_heads * (d / 2) / (dtype == REKV_BF16 ? 8 : 4);
     int gy = (units + GATHER_THREADS * 4 - 1) / (GATHER_THREADS * 4);      // about 4 units per thread
     if (gy < 1) gy = 1;

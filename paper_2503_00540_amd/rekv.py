@@ -23,7 +23,7 @@ _DTYPES = {"f32": (REKV_F32, torch.float32), "bf16": (REKV_BF16, torch.bfloat16)
 # Every entry point include/rekv.h declares.
 SYMBOLS = ("rekv_create", "rekv_destroy", "rekv_last_error", "rekv_encode_chunk",
            "rekv_frame_keys", "rekv_retrieve_topk", "rekv_gather_kv", "rekv_qa_attention",
-           "rekv_decode_attention", "rekv_decode_attention_noalloc", "rekv_block_keys", "rekv_expand_blocks", "rekv_retrieve_external", "rekv_attention_indexed", "rekv_gather_kv_rope", "rekv_gather_kv_layers",
+           "rekv_decode_attention", "rekv_decode_attention_noalloc", "rekv_block_keys", "rekv_expand_blocks", "rekv_retrieve_external", "rekv_attention_indexed", "rekv_gather_kv_rope", "rekv_gather_kv_layers", "rekv_attention_indexed_rope",
            "rekv_offload_kv", "rekv_offload_wait", "rekv_probe_copy", "rekv_probe_mfma")
 
 
@@ -78,8 +78,11 @@ def lib() -> ctypes.CDLL:
                                          c_void_p, c_void_p]
     L.rekv_gather_kv_layers.argtypes = [c_void_p, POINTER(c_void_p), POINTER(c_void_p), c_int32, c_int32, c_void_p,
                                         c_int32, c_int32, c_void_p, c_void_p, c_void_p]
-    L.rekv_gather_kv_rope.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_int32, c_int32, c_void_p,
+    L.rekv_gather_kv_rope.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_int32, c_int32, c_void_p,
                                       c_void_p, ctypes.c_double, c_int32, c_int32, c_int64, c_int32, c_int64, c_void_p]
+    L.rekv_attention_indexed_rope.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_int64, c_int32,
+                                              c_void_p, c_void_p, ctypes.c_double, c_int32, c_int32, c_int64, c_int32, c_int64,
+                                              c_void_p, c_void_p, c_int64, c_int32, c_int32, c_int32, c_void_p, c_void_p]
     L.rekv_offload_kv.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32,
                                   c_void_p]
     L.rekv_offload_wait.argtypes = [c_void_p]
@@ -299,8 +302,9 @@ class Rekv:
     def gather_kv_rope(self, src_k, src_v, idx, n_src_frames: int | None = None, mode: str = "consecutive",
                        pos_offset: int = 0, src_rotated: bool = False, src_pos_offset: int = 0,
                        base: float = 10000.0, layout: str = "half"):
-        """rekv_gather_kv_rope: idx [n_questions, k] int32 on the device, source in HBM."""
+        """rekv_gather_kv_rope: idx [n_questions, k] int32 on the device; source in HBM or pinned on the host."""
         kh = (self.n_kv_heads, self.head_dim)
+        on_host = not src_k.is_cuda
         nf = src_k.shape[0] // self.tokens_per_frame if n_src_frames is None else n_src_frames
         if src_k.shape[0] < nf * self.tokens_per_frame or src_v.shape != src_k.shape:
             raise ValueError("src_k / src_v are shorter than n_src_frames frames")
@@ -310,12 +314,47 @@ class Rekv:
         shape = (nq, k * self.tokens_per_frame, *kh)
         dst_k = torch.empty(shape, dtype=self.torch_dtype, device=idx.device)
         dst_v = torch.empty(shape, dtype=self.torch_dtype, device=idx.device)
+        ps = (self._pinned(src_k, kh, "src_k"), self._pinned(src_v, kh, "src_v")) if on_host else \
+             (self._dev(src_k, last=kh, name="src_k"), self._dev(src_v, last=kh, name="src_v"))
         self._check(self._lib.rekv_gather_kv_rope(
-            self._h, self._dev(src_k, last=kh, name="src_k"), self._dev(src_v, last=kh, name="src_v"), nf,
+            self._h, ps[0], ps[1], int(on_host), nf,
             idx.data_ptr(), nq, k, dst_k.data_ptr(), dst_v.data_ptr(), base,
             {"half": 0, "interleaved": 1}[layout], {"consecutive": 0, "static": 1}[mode], pos_offset,
             int(src_rotated), src_pos_offset, _stream()))
         return dst_k, dst_v
+
+    def attention_indexed_rope(self, q, k_src, v_src, idx, k_text, v_text, n_text_tokens: int,
+                               n_src_frames: int | None = None, n_sel=None, mode: str = "consecutive",
+                               pos_offset: int = 0, src_rotated: bool = False, src_pos_offset: int = 0,
+                               base: float = 10000.0, layout: str = "half", k_pos=None, out=None):
+        """rekv_attention_indexed_rope: idx [n_questions, n_ret_frames] int32 (contiguous, device).
+        Returns (out, k_pos)."""
+        qh, kh = (self.n_q_heads, self.head_dim), (self.n_kv_heads, self.head_dim)
+        if q.dim() != 4 or k_text.dim() != 4 or idx.dim() != 2 or idx.dtype != torch.int32 or not idx.is_cuda \
+                or not idx.is_contiguous():
+            raise ValueError("q, k_text must be 4-d; idx a contiguous device tensor [n_questions, n_ret_frames] int32")
+        nq, n_new = q.shape[0], q.shape[1]
+        n_ret = idx.shape[1]
+        if idx.shape[0] != nq or k_text.shape[0] != nq or v_text.shape != k_text.shape:
+            raise ValueError("idx, k_text, v_text must have one row per question")
+        nf = k_src.shape[0] // self.tokens_per_frame if n_src_frames is None else n_src_frames
+        if k_src.shape[0] < nf * self.tokens_per_frame or v_src.shape != k_src.shape:
+            raise ValueError("k_src / v_src are shorter than n_src_frames frames")
+        shape = (nq, n_ret * self.tokens_per_frame, *kh)
+        k_pos = torch.empty(shape, dtype=self.torch_dtype, device=q.device) if k_pos is None else k_pos
+        if tuple(k_pos.shape) != shape:
+            raise ValueError(f"k_pos must have shape {shape}")
+        out = torch.empty_like(q) if out is None else out
+        if out.shape != q.shape:
+            raise ValueError("out must have the shape of q")
+        self._check(self._lib.rekv_attention_indexed_rope(
+            self._h, self._dev(q, last=qh, name="q"), self._dev(k_src, last=kh, name="k_src"),
+            self._dev(v_src, last=kh, name="v_src"), nf, idx.data_ptr(), n_ret, n_ret, self._n_sel(n_sel, nq),
+            self._dev(k_pos, last=kh, name="k_pos"), base, {"half": 0, "interleaved": 1}[layout],
+            {"consecutive": 0, "static": 1}[mode], pos_offset, int(src_rotated), src_pos_offset,
+            self._dev(k_text, last=kh, name="k_text"), self._dev(v_text, last=kh, name="v_text"),
+            k_text.shape[1], n_text_tokens, nq, n_new, self._dev(out, last=qh, name="out"), _stream()))
+        return out, k_pos
 
     def qa_attention(self, q, k_ret, v_ret, k_self, v_self, out=None, n_sel=None):
         """q [n_questions, N_q, Hq, D]; k_ret/v_ret [n_questions, n_ret, Hkv, D]; k_self/v_self

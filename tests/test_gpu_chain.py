@@ -299,3 +299,62 @@ def test_gather_of_several_layers_in_one_launch():
             assert host(gk)[layer, q, :n].tobytes() == rk.astype(np.float64).tobytes()
             assert host(gv)[layer, q, :n].tobytes() == rv.astype(np.float64).tobytes()
             assert not host(gk)[layer, q, n:].any()
+
+
+# ----------------------------------------------------------------------------------------
+# position policy of the retrieved keys on the gather-free path and for offloaded KV
+# ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("w0,mode,src_rotated,layout", [
+    (W.C1, "consecutive", False, "half"), (W.C1, "static", True, "half"), (W.C4, "consecutive", True, "interleaved"),
+    (W.C0.scaled(tokens_per_frame=7, n_q_heads=4, n_kv_heads=2, name="C0p"), "consecutive", True, "half")],
+    ids=["7B-plain-cache", "7B-static", "72B-interleaved", "f32"])
+def test_in_place_attention_with_repositioned_keys(w0, mode, src_rotated, layout):
+    """Values read in place through the frame list, keys turned to consecutive (or one static)
+    position by the pre-pass: against the oracle's gather-with-positions followed by Eq. 3.  The
+    second question's selection is shorter than the list (n_sel)."""
+    w = w0.scaled(n_frames=24, n_q_tokens=11)
+    nf = w.tokens_per_frame
+    r = Rekv.for_workload(w)
+    k, v = W.frames_k(w, 0, w.n_frames), W.frames_v(w, 0, w.n_frames)
+    src_off = 700_000
+    if src_rotated:
+        k = O.apply_rope(k, src_off + np.arange(k.shape[0]), layout=layout)
+        k = W.round_to_bf16(k) if w.dtype == "bf16" else k.astype(np.float32).astype(np.float64)
+    idx = np.array([[2, 5, 6, 11, 20], [0, 9, 23, -1, -1]], dtype=np.int32)
+    n_sel = torch.tensor([5, 3], dtype=torch.int32, device=DEV)
+    qs = [W.question_qkv(w, i) for i in range(2)]
+    dq, dqk, dqv = (dev(np.stack([x[j] for x in qs]), w) for j in range(3))
+    out, k_pos = r.attention_indexed_rope(dq, dev(k, w), dev(v, w), torch.from_numpy(idx).to(DEV), dqk, dqv, w.n_q_tokens,
+                                          n_src_frames=w.n_frames, n_sel=n_sel, mode=mode, pos_offset=35,
+                                          src_rotated=src_rotated, src_pos_offset=src_off, layout=layout)
+    out = host(out)
+    for i in range(2):
+        frames = [f for f in idx[i] if f >= 0]
+        rk, rv = O.gather_kv_rope(k, v, frames, nf, mode=mode, pos_offset=35, src_rotated=src_rotated,
+                                  src_pos_offset=src_off, layout=layout)
+        # the oracle's keys, rounded once to the storage type as the pre-pass stores them
+        rk = W.round_to_bf16(rk) if w.dtype == "bf16" else rk.astype(np.float32).astype(np.float64)
+        ref = O.decode_attention(qs[i][0], rk, rv, qs[i][1], qs[i][2])
+        err = np.abs(out[i] - ref).max()
+        assert err < TOL[w.dtype], (i, err)
+    # the same through gather-with-positions + attention of this library
+    gk, gv = r.gather_kv_rope(dev(k, w), dev(v, w), torch.from_numpy(idx).to(DEV), n_src_frames=w.n_frames, mode=mode,
+                              pos_offset=35, src_rotated=src_rotated, src_pos_offset=src_off, layout=layout)
+    assert torch.equal(gk, k_pos)
+    via_gather = host(r.decode_attention(dq, gk, gv, dqk, dqv, w.n_q_tokens, n_sel=n_sel))
+    assert np.abs(via_gather - out).max() < 1e-6 + (4e-3 if w.dtype == "bf16" else 0)
+
+
+def test_position_policy_on_offloaded_kv():
+    """The gather with positions reading pinned host arenas (offloaded KV): bit-equal to the same
+    call on HBM arenas."""
+    w = W.C1.scaled(n_frames=20)
+    k, v = W.frames_k(w, 0, w.n_frames), W.frames_v(w, 0, w.n_frames)
+    r = Rekv.for_workload(w)
+    dk, dv = dev(k, w), dev(v, w)
+    hk, hv = dk.cpu().pin_memory(), dv.cpu().pin_memory()
+    idx = torch.tensor([[17, 3, 4, 9, -1], [0, 19, 18, -1, -1]], dtype=torch.int32, device=DEV)
+    a = r.gather_kv_rope(dk, dv, idx, mode="consecutive", pos_offset=35)
+    b = r.gather_kv_rope(hk, hv, idx, mode="consecutive", pos_offset=35)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
