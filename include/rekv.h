@@ -354,7 +354,9 @@ rekv_status rekv_attention_indexed_rope(rekv_ctx* ctx, const void* q, const void
  * first_frame of the device arrays, to the same frame positions of the pinned host arrays.
  * The copies run on the context's side stream after everything queued on `stream` so far;
  * `stream` does not wait for them.  rekv_offload_wait() blocks the host until all offloads
- * issued on this context have landed.
+ * issued on this context have landed; rekv_offload_join() instead makes `stream` wait for them
+ * on the device (the host does not block), so that work queued on `stream` afterwards may
+ * overwrite the device arrays - the slots of evicted frames - while the host copies stay intact.
  *
  *   dev_k, dev_v    [>= (first_frame + n_frames) * N_f, Hkv, D] in HBM
  *   host_k, host_v  same indexing, pinned host memory (host pointers)
@@ -362,6 +364,7 @@ rekv_status rekv_attention_indexed_rope(rekv_ctx* ctx, const void* q, const void
 rekv_status rekv_offload_kv(rekv_ctx* ctx, const void* dev_k, const void* dev_v, void* host_k,
                             void* host_v, int64_t first_frame, int32_t n_frames, void* stream);
 rekv_status rekv_offload_wait(rekv_ctx* ctx);
+rekv_status rekv_offload_join(rekv_ctx* ctx, void* stream);
 
 /*
  * Measurement probes.  They are not operations of the method: they show what this GPU

@@ -652,6 +652,13 @@ rekv_status rekv_offload_wait(rekv_ctx* c) {
     return e == hipSuccess ? REKV_OK : fail_hip(c, "rekv_offload_wait", e);
 }
 
+rekv_status rekv_offload_join(rekv_ctx* c, void* stream) {
+    if (!c) return REKV_ERR_INVALID_ARG;
+    hipError_t e = hipEventRecord(c->ev_side, c->side);
+    if (e == hipSuccess) e = hipStreamWaitEvent(static_cast<hipStream_t>(stream), c->ev_side, 0);
+    return e == hipSuccess ? REKV_OK : fail_hip(c, "rekv_offload_join", e);
+}
+
 rekv_status rekv_probe_copy(rekv_ctx* c, void* dst, const void* src, int64_t n_bytes, void* stream) {
     if (!c) return REKV_ERR_INVALID_ARG;
     if (!dst || !src) return fail(c, REKV_ERR_INVALID_ARG, "rekv_probe_copy: null pointer");

@@ -24,7 +24,7 @@ _DTYPES = {"f32": (REKV_F32, torch.float32), "bf16": (REKV_BF16, torch.bfloat16)
 SYMBOLS = ("rekv_create", "rekv_destroy", "rekv_last_error", "rekv_encode_chunk",
            "rekv_frame_keys", "rekv_retrieve_topk", "rekv_gather_kv", "rekv_qa_attention",
            "rekv_decode_attention", "rekv_decode_attention_noalloc", "rekv_block_keys", "rekv_expand_blocks", "rekv_retrieve_external", "rekv_attention_indexed", "rekv_gather_kv_rope", "rekv_gather_kv_layers", "rekv_attention_indexed_rope",
-           "rekv_offload_kv", "rekv_offload_wait", "rekv_probe_copy", "rekv_probe_mfma")
+           "rekv_offload_kv", "rekv_offload_wait", "rekv_offload_join", "rekv_probe_copy", "rekv_probe_mfma")
 
 
 class RekvShape(ctypes.Structure):
@@ -86,6 +86,7 @@ def lib() -> ctypes.CDLL:
     L.rekv_offload_kv.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32,
                                   c_void_p]
     L.rekv_offload_wait.argtypes = [c_void_p]
+    L.rekv_offload_join.argtypes = [c_void_p, c_void_p]
     L.rekv_probe_copy.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_void_p]
     L.rekv_probe_mfma.argtypes = [c_void_p, c_void_p, c_int32, c_int32, POINTER(ctypes.c_double), c_void_p]
     for name in SYMBOLS[3:]:
@@ -443,6 +444,10 @@ class Rekv:
 
     def offload_wait(self):
         self._check(self._lib.rekv_offload_wait(self._h))
+
+    def offload_join(self):
+        """rekv_offload_join: the current stream waits (on the device) for the offloads issued so far."""
+        self._check(self._lib.rekv_offload_join(self._h, _stream()))
 
     def probe_copy(self, dst: torch.Tensor, src: torch.Tensor) -> int:
         """rekv_probe_copy: streaming copy of src into dst; returns the bytes copied."""

@@ -58,6 +58,7 @@ def test_entry_points_refuse_a_null_context():
     assert L.rekv_gather_kv_rope(None, None, None, 0, 1, None, 1, 1, None, None, 10000.0, 0, 0, 0, 0, 0, None) == 1
     assert L.rekv_offload_kv(None, None, None, None, None, 0, 1, None) == 1
     assert L.rekv_offload_wait(None) == 1
+    assert L.rekv_offload_join(None, None) == 1
 
 
 def test_missing_library_fails_loudly(monkeypatch):

@@ -270,6 +270,32 @@ def test_offload_waits_for_the_kernel_that_writes_the_kv():
     torch.cuda.synchronize()
 
 
+def test_offload_join_orders_later_writes_behind_the_copies():
+    """The slots of offloaded frames are overwritten on the caller's stream right after
+    rekv_offload_join, with no host wait in between: the host copies must hold the original
+    values.  The buffers are large enough (37 MB each) that the copies are still running when
+    the overwrite is queued."""
+    w = W.C1.scaled(n_frames=96)
+    nf = w.tokens_per_frame
+    shape = (w.n_frames * nf, w.n_kv_heads, w.head_dim)
+    g = torch.Generator(device=DEV).manual_seed(31)
+    dk = torch.randn(shape, device=DEV, generator=g).to(torch.bfloat16)
+    dv = torch.randn(shape, device=DEV, generator=g).to(torch.bfloat16)
+    keep_k, keep_v = dk.clone(), dv.clone()
+    hk = torch.zeros(shape, dtype=torch.bfloat16).pin_memory()
+    hv = torch.zeros(shape, dtype=torch.bfloat16).pin_memory()
+    r = Rekv.for_workload(w)
+    torch.cuda.synchronize()
+    r.offload_kv(dk, dv, hk, hv, 0, w.n_frames)
+    r.offload_join()
+    dk.fill_(7.0)                      # queued behind the join on the caller's stream
+    dv.fill_(-7.0)
+    r.offload_wait()
+    torch.cuda.synchronize()
+    assert torch.equal(hk, keep_k.cpu()) and torch.equal(hv, keep_v.cpu())
+    assert bool((dk == 7.0).all()) and bool((dv == -7.0).all())
+
+
 # ----------------------------------------------------------------------------------------
 # per-layer gather in one launch
 # ----------------------------------------------------------------------------------------
