@@ -27,8 +27,8 @@ N_SIMD, N_XCD = 1024, 8
 
 def _one(d, pattern):
     hits = sorted(glob.glob(os.path.join(d, "**", pattern), recursive=True))
-    if not hits:
-        raise FileNotFoundError(f"no {pattern} under {d}")
+    if len(hits) != 1:
+        raise FileNotFoundError(f"expected one {pattern} under {d}, found {len(hits)}")
     return hits[0]
 
 
@@ -96,17 +96,31 @@ def cmd_trace(argv):
     table, groups = trace_table(d)
     text = ["rocprofv3 kernel trace, library kernels only, grouped by kernel and total thread count.  MI355X, ROCm 7.2.", "",
             f"command: {command}", f"source : {os.path.basename(_one(d, '*kernel_trace.csv'))}", "", table, ""]
+    b = None
+    if bench_json:
+        import json
+        b = json.loads(open(bench_json).read().strip().splitlines()[-1])
     enc = [(k, v) for k, v in groups.items() if "attn_bf16_kernel<128, true" in k[0]]
     if enc:
         (name, grid), v = max(enc, key=lambda kv: kv[0][1])
         avg = sum(v) / len(v)
-        text.append(f"Encode launch of the whole stream: {name} with {grid} threads, {len(v)} calls, average {avg / 1e3:.1f} us "
-                    f"(the rows of the same kernel with fewer threads are the one-chunk-per-launch streaming calls).")
-        text.append(f"C1: {ENCODE_FLOP_C1:.4e} algorithmic FLOP per launch -> {ENCODE_FLOP_C1 / avg / 1e3:.0f} TFLOP/s = "
-                    f"{100 * ENCODE_FLOP_C1 / avg / 1e3 / 2500:.1f} % of the 2.5 PFLOP/s bf16 MFMA peak (only meaningful for a C1 run).")
-    if bench_json:
-        import json
-        b = json.loads(open(bench_json).read().strip().splitlines()[-1])
+        text.append(f"Encode launch of the timed step: {name} with {grid} threads, {len(v)} calls, average {avg / 1e3:.1f} us "
+                    f"(rows of the same kernel with fewer threads: the one-chunk-per-launch streaming calls, and for the "
+                    f"offloaded-KV workload the stream's first, shorter segment).")
+        if "--no-extras" not in command:
+            text.append("This run includes the benchmark's extras: the launches on all-zero inputs are among those calls and "
+                        "pull the average down (they are the fastest ones); the trace of the --no-extras command holds the "
+                        "timed configuration alone.")
+        # the workload's own algorithmic FLOP per launch, as the benchmark line of the same run states it
+        flop = b["roofline"]["algorithmic_flop_per_launch"] if b else ENCODE_FLOP_C1
+        what = b["config"]["workload"].split(":")[0] if b else "C1-7B-1layer"
+        text.append(f"{what}: {flop:.4e} algorithmic FLOP per launch -> {flop / avg / 1e3:.0f} TFLOP/s = "
+                    f"{100 * flop / avg / 1e3 / 2500:.1f} % of the 2.5 PFLOP/s bf16 MFMA peak.")
+    if b and "offloaded" in b["config"]["workload"] and enc:
+        text.append(f"Under the profiler the offload copies on the side stream slow the encode launches they overlap: the "
+                    f"step's first launch, which overlaps none, is the minimum ({min(v) / 1e3:.1f} us); without the profiler "
+                    f"all launches of this workload take about that long (benchmark line of a plain run: roofline.frac 0.41-0.43).")
+    if b:
         text.append(f"bench.py's own HIP-event average of the encode launch in the same run: {b['roofline']['avg_launch_ms'] * 1e3:.1f} us; "
                     f"roofline.frac {b['roofline']['frac']:.3f}.")
     open(out, "w").write("\n".join(text) + "\n")
