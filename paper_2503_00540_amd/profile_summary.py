@@ -2,7 +2,7 @@
 
     python -m paper_2503_00540_amd.profile_summary trace   <dir> <out.txt> "<command>" [--bench-json FILE]
     python -m paper_2503_00540_amd.profile_summary traffic <fetch_dir> <write_dir> <out.txt> "<fetch cmd>" "<write cmd>"
-    python -m paper_2503_00540_amd.profile_summary cycles  <dir> [<dir> ...] <out.txt> "<command>"
+    python -m paper_2503_00540_amd.profile_summary cycles  <dir> [<dir> ...] <out.txt> "<command>" [--zero-run <dir> "<command>"]
 
 <dir> is a rocprofv3 output directory (-d) holding *_kernel_trace.csv and, for counter runs,
 *_counter_collection.csv.  Kernels are grouped by name and grid size, because one kernel name
@@ -151,7 +151,34 @@ def cmd_traffic(argv):
     open(out, "w").write("\n".join(text) + "\n")
 
 
+def _zero_input_block(d, command):
+    """Clock and MFMA-busy share of the encode launch on all-zero inputs: in a run of the default command
+    (extras on) the whole-stream encode kernel is launched on the benchmark's inputs and, for the zero-input
+    diagnostic, on zeros; the zero-input launches are the shortest dispatches of that (kernel, thread count)."""
+    per = load_counters(d)
+    enc = [(key, disp) for key, disp in per.items() if "attn_bf16_kernel<128, true" in key[0]]
+    if not enc:
+        return []
+    (name, grid), disp = max(enc, key=lambda kv: kv[0][1])
+    vals = sorted(disp.values(), key=lambda v: v["__ns"])
+    lines = ["== encode launch on all-zero inputs against the same launch on the benchmark's inputs",
+             f"  command: {command}",
+             f"  {name}, {grid} threads, {len(vals)} dispatches; shortest = zero inputs, longest = benchmark inputs"]
+    for label, v in (("zero inputs", vals[0]), ("benchmark inputs", vals[-1])):
+        cyc = v["GRBM_GUI_ACTIVE"] / N_XCD
+        lines.append(f"  {label:17s}: {v['__ns'] / 1e3:8.1f} us, {cyc:.4g} clocks -> {cyc / v['__ns']:.2f} GHz; MFMA pipes busy "
+                     f"{100 * v['SQ_VALU_MFMA_BUSY_CYCLES'] / N_SIMD / cyc:.1f} %; SQ_INSTS_MFMA {v['SQ_INSTS_MFMA']:.6g}")
+    lines.append("  Same instruction stream and about the same number of clocks; the clock the chip grants differs.")
+    lines.append("")
+    return lines
+
+
 def cmd_cycles(argv):
+    zero_dir = zero_cmd = None
+    if "--zero-run" in argv:
+        i = argv.index("--zero-run")
+        zero_dir, zero_cmd = argv[i + 1], argv[i + 2]
+        argv = argv[:i] + argv[i + 3:]
     dirs, out, command = argv[:-2], argv[-2], argv[-1]
     text = ["Cycle budget of the encode launch (all chunks of the C1 stream) and of the register-resident MFMA probe, from rocprofv3",
             "counter runs of the benchmark.  SQ_*_CYCLES and SQ_ACTIVE_* / SQ_WAIT_* count in units of 4 clocks, summed over the chip;",
@@ -190,6 +217,8 @@ def cmd_cycles(argv):
         if "SQ_INSTS_VALU" in merged and "SQ_INSTS_MFMA" in merged:
             text.append(f"  vector instructions per MFMA (SQ_INSTS_VALU / SQ_INSTS_MFMA, MFMAs included) = {merged['SQ_INSTS_VALU'] / merged['SQ_INSTS_MFMA']:.2f}")
         text.append("")
+    if zero_dir:
+        text += _zero_input_block(zero_dir, zero_cmd)
     open(out, "w").write("\n".join(text) + "\n")
 
 
