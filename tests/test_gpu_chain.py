@@ -27,7 +27,8 @@ def host(t):
 # ----------------------------------------------------------------------------------------
 # Eq. 3 when fewer than k frames were selected: the padding must stay out of the softmax
 # ----------------------------------------------------------------------------------------
-@pytest.mark.parametrize("w0", [W.C1, W.C0.scaled(n_q_heads=4, n_kv_heads=2, name="C0-2kv")], ids=["bf16", "f32"])
+@pytest.mark.parametrize("w0", [W.C1, W.C0.scaled(n_q_heads=4, n_kv_heads=2, name="C0-2kv"),
+                                W.C1.scaled(n_q_heads=14, n_kv_heads=2, head_dim=64, name="C1-0.5B")], ids=["bf16", "f32", "bf16-D64"])
 def test_short_selections_through_gather_and_in_place_attention(w0):
     """Block retrieval on a stream whose last block is short: question 0 points at that block and
     gets fewer frames than question 1, in one batch.  retrieve -> expand -> gather -> QA attention
@@ -332,8 +333,9 @@ def test_gather_of_several_layers_in_one_launch():
 # ----------------------------------------------------------------------------------------
 @pytest.mark.parametrize("w0,mode,src_rotated,layout", [
     (W.C1, "consecutive", False, "half"), (W.C1, "static", True, "half"), (W.C4, "consecutive", True, "interleaved"),
-    (W.C0.scaled(tokens_per_frame=7, n_q_heads=4, n_kv_heads=2, name="C0p"), "consecutive", True, "half")],
-    ids=["7B-plain-cache", "7B-static", "72B-interleaved", "f32"])
+    (W.C0.scaled(tokens_per_frame=7, n_q_heads=4, n_kv_heads=2, name="C0p"), "consecutive", True, "half"),
+    (W.C1.scaled(n_q_heads=14, n_kv_heads=2, head_dim=64, name="C1-0.5B"), "consecutive", True, "half")],
+    ids=["7B-plain-cache", "7B-static", "72B-interleaved", "f32", "0.5B-D64"])
 def test_in_place_attention_with_repositioned_keys(w0, mode, src_rotated, layout):
     """Values read in place through the frame list, keys turned to consecutive (or one static)
     position by the pre-pass: against the oracle's gather-with-positions followed by Eq. 3.  The
