@@ -117,6 +117,52 @@ def test_young_stream_selection_of_everything():
         assert np.abs(out0[i] - ref).max() < TOL["bf16"], i
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_random_selection_lengths_sweep(dtype):
+    """Twelve random shapes per storage type: every question of a batch keeps a random number of its k
+    list entries (none at all included), the rest is -1 padding.  Gathered QA attention, the decode
+    step and the in-place variant against the oracle on the frames that are kept."""
+    rng = np.random.default_rng(77 if dtype == "bf16" else 78)
+    base = W.C1 if dtype == "bf16" else W.C0.scaled(n_q_heads=4, n_kv_heads=2, name="C0-2kv")
+    for case in range(12):
+        d = int(rng.choice([64, 128])) if dtype == "bf16" else int(rng.choice([32, 64, 128]))
+        hkv = int(rng.choice([1, 2, 4]))
+        group = int(rng.choice([1, 4, 7]))
+        w = base.scaled(n_frames=int(rng.integers(6, 30)), tokens_per_frame=int(rng.integers(3, 45)),
+                        n_q_tokens=int(rng.integers(1, 40)), n_q_heads=hkv * group, n_kv_heads=hkv, head_dim=d,
+                        name=f"sweep-{dtype}-{case}")
+        nf, nq, k = w.tokens_per_frame, int(rng.integers(1, 4)), int(rng.integers(1, 6))
+        kf, vf = W.frames_k(w, 0, w.n_frames), W.frames_v(w, 0, w.n_frames)
+        idx = np.full((nq, k), -1, dtype=np.int32)
+        keep = rng.integers(0, k + 1, size=nq)
+        for i in range(nq):
+            idx[i, :keep[i]] = np.sort(rng.choice(w.n_frames, size=keep[i], replace=False))
+        shape_q = (nq, w.n_q_tokens, w.n_q_heads, d)
+        shape_kv = (nq, w.n_q_tokens, hkv, d)
+        q, qk, qv = rng.standard_normal(shape_q), rng.standard_normal(shape_kv), rng.standard_normal(shape_kv)
+        if dtype == "bf16":
+            q, qk, qv = W.round_to_bf16(q), W.round_to_bf16(qk), W.round_to_bf16(qv)
+        else:
+            q, qk, qv = (x.astype(np.float32).astype(np.float64) for x in (q, qk, qv))
+        r = Rekv.for_workload(w)
+        dk, dv, didx = dev(kf, w), dev(vf, w), torch.from_numpy(idx).to(DEV)
+        n_sel = torch.from_numpy(keep.astype(np.int32)).to(DEV)
+        dq, dqk, dqv = dev(q, w), dev(qk, w), dev(qv, w)
+        print(f"case {w.name}: frames {w.n_frames} x {nf}, Hq/Hkv/D {w.n_q_heads}/{hkv}/{d}, {nq} question(s) of "
+              f"{w.n_q_tokens}, k {k}, kept {keep.tolist()}", flush=True)
+        gk, gv = r.gather_kv(dk, dv, didx, n_src_frames=w.n_frames)
+        outs = {"qa": host(r.qa_attention(dq, gk, gv, dqk, dqv, n_sel=n_sel)),
+                "decode": host(r.decode_attention(dq, gk, gv, dqk, dqv, w.n_q_tokens, n_sel=n_sel)),
+                "indexed": host(r.attention_indexed(dq, dk, dv, didx, k, dqk, dqv, w.n_q_tokens,
+                                                    n_src_frames=w.n_frames, n_sel=n_sel))}
+        for i in range(nq):
+            rk, rv = O.gather_kv(kf, vf, [int(f) for f in idx[i, :keep[i]]], nf)
+            ref = O.qa_attention(q[i], rk, rv, qk[i], qv[i])
+            for name, o in outs.items():
+                err = np.abs(o[i] - ref).max()
+                assert err < TOL[dtype], (w.name, name, i, int(keep[i]), err)
+
+
 # ----------------------------------------------------------------------------------------
 # the running maximum rises in every tile: the rescaling of partial sums is exercised
 # ----------------------------------------------------------------------------------------
