@@ -268,6 +268,32 @@ def test_external_retrieval_matches_oracle(dim, n_frames, nq, tau, k):
         r.retrieve_external(torch.zeros((4, 6), device=DEV), torch.zeros((1, 6), device=DEV), 1)   # dim % 4
 
 
+def test_external_retrieval_random_shapes_sweep():
+    """Sixteen random (dim, frames, questions, k, tau): vector lengths that are no multiple of the
+    scoring kernels' column slabs, frame and question counts that leave ragged tiles, one question or
+    many on the shared table."""
+    rng = np.random.default_rng(2024)
+    r = Rekv.for_workload(W.C1)
+    for case in range(16):
+        dim = 4 * int(rng.integers(1, 330))
+        n_frames = int(rng.integers(1, 3000))
+        nq = int(rng.choice([1, 2, 3, 4, 5, 31, 33, 70]))
+        k = int(rng.integers(1, 70))
+        tau = float(rng.choice([1.0, 0.07, 0.5]))
+        emb = rng.standard_normal((n_frames, dim)).astype(np.float32)
+        qe = rng.standard_normal((nq, dim)).astype(np.float32)
+        print(f"case {case}: dim {dim}, {n_frames} frames, {nq} question(s), k {k}, tau {tau}", flush=True)
+        idx, n_sel, scores = r.retrieve_external(torch.from_numpy(emb).to(DEV), torch.from_numpy(qe).to(DEV), k,
+                                                 tau=tau, want_scores=True)
+        sc = host(scores)
+        for i in range(nq):
+            _, ref_s = O.retrieve_external(emb, qe[i], k, tau)
+            assert np.abs(sc[i] - ref_s).max() < 1e-5 / tau, (case, i)
+            check_topk(idx[i].cpu().numpy(), ref_s, k, gap=1e-3 / tau)
+            np.testing.assert_array_equal(idx[i].cpu().numpy()[:min(k, n_frames)], O.topk_frames(sc[i], k))
+            assert int(n_sel[i]) == min(k, n_frames)
+
+
 @pytest.mark.parametrize("n_frames,k", [(4097, 64), (10000, 1), (10000, 4096), (70000, 333)],
                          ids=["just-past-the-resident-limit", "k1", "largest-k", "70k-frames"])
 def test_topk_on_tables_longer_than_the_resident_limit(n_frames, k):
