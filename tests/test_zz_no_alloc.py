@@ -49,3 +49,33 @@ def test_no_alloc_decode_refuses_what_the_ordinary_call_refuses():
     q, kr, vr, kt, vt = _inputs(w, 1, 2, 20, 1, 3)
     with pytest.raises(RekvError):
         r.decode_attention(q, kr, vr, kt, vt, 0, no_alloc=True)            # fewer text rows than new tokens
+
+
+def test_no_alloc_decode_captures_into_a_hip_graph_on_a_fresh_context():
+    """What the entry point is for: a context that has never grown a workspace is captured into a HIP
+    graph (the allocating call could not be: its first use allocates), and every replay, with eager
+    library work and synchronisations in between, gives the eager result bit for bit."""
+    w = W.C1
+    q, kr, vr, kt, vt = _inputs(w, 1, 16, 96, 1, 5)          # split key range: the scratch is in use
+    n_text = 96
+    ref = Rekv.for_workload(w).decode_attention(q, kr, vr, kt, vt, n_text)      # another context
+    fresh = Rekv.for_workload(w)
+    out = torch.empty_like(q)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            fresh.decode_attention(q, kr, vr, kt, vt, n_text, out=out, no_alloc=True)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for _ in range(4):
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref)
+        other = fresh.decode_attention(q, kr, vr, kt, vt, n_text, no_alloc=True)    # eager use of the same scratch
+        torch.cuda.synchronize()
+        assert torch.equal(other, ref)
