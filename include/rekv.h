@@ -350,8 +350,9 @@ rekv_status rekv_attention_indexed_rope(rekv_ctx* ctx, const void* q, const void
 /*
  * Offload of encoded KV to RAM (the paragraph after Eq. 1: every frame's KV is kept, and what
  * leaves the local window moves off the GPU; appendix "Multi-processing Serving": the encoder
- * process hands the stream's KV to the answering processes through host memory).  Copies n_frames whole frames of K and V, starting at frame
- * first_frame of the device arrays, to the same frame positions of the pinned host arrays.
+ * process hands the stream's KV to the answering processes through host memory).  Copies
+ * n_frames whole frames of K and V, starting at frame first_frame of the device arrays, to the
+ * same frame positions of the pinned host arrays.
  * The copies run on the context's side stream after everything queued on `stream` so far;
  * `stream` does not wait for them.  rekv_offload_wait() blocks the host until all offloads
  * issued on this context have landed; rekv_offload_join() instead makes `stream` wait for them
